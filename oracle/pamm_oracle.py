@@ -1,0 +1,166 @@
+"""ctypes front end of the fp64 CPU oracle in ``pamm_oracle.c``.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's CPU-baseline leg, never by the product package.  The arithmetic is
+all in the C file (which cites the passages of the paper it follows); this
+module only compiles it with gcc, marshals numpy arrays and returns numpy
+arrays.  It imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pamm_oracle.c")
+_LIB = os.path.join(_HERE, "libpamm_oracle.so")
+
+F32, BF16, F64 = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over rows).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, i32p, f64p, vp = ctypes.c_int64, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double), ctypes.c_void_p
+        lib.pamm_oracle_threads.restype = ctypes.c_int
+        lib.pamm_oracle_set_threads.argtypes = [ctypes.c_int]
+        lib.pamm_oracle_splitmix64.argtypes = [ctypes.c_uint64, i64, ctypes.POINTER(ctypes.c_uint64)]
+        lib.pamm_oracle_sample.argtypes = [i64, i64, ctypes.c_uint64, i32p]
+        lib.pamm_oracle_sample.restype = ctypes.c_int
+        lib.pamm_oracle_compress.argtypes = [vp, ctypes.c_int, i64, i64, i64, i32p, f64p, i32p, f64p, f64p, f64p, i32p]
+        lib.pamm_oracle_compress.restype = ctypes.c_int
+        lib.pamm_oracle_grad.argtypes = [f64p, i32p, f64p, vp, ctypes.c_int, i64, i64, i64, i64, f64p, f64p]
+        lib.pamm_oracle_grad.restype = ctypes.c_int
+        lib.pamm_oracle_score.argtypes = [vp, ctypes.c_int, i64, i64, i64]
+        lib.pamm_oracle_score.restype = ctypes.c_double
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().pamm_oracle_threads())
+
+
+def set_threads(t: int) -> None:
+    _load().pamm_oracle_set_threads(int(t))
+
+
+def as_raw(x):
+    """(contiguous numpy array, element-type code) for a matrix given as a numpy array
+    (float32, float64, or uint16 holding bfloat16 bit patterns) or as a CPU torch tensor
+    (float32, float64 or bfloat16).  No value is changed."""
+    if not isinstance(x, np.ndarray):
+        import torch  # only needed to re-view bfloat16 storage
+
+        t = x.detach().cpu().contiguous()
+        if t.dtype == torch.bfloat16:
+            x = t.view(torch.int16).numpy().view(np.uint16)
+        else:
+            x = t.numpy()
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.float32:
+        return x, F32
+    if x.dtype == np.uint16:
+        return x, BF16
+    if x.dtype == np.float64:
+        return x, F64
+    raise TypeError(f"unsupported element type {x.dtype}")
+
+
+def to_f64(x) -> np.ndarray:
+    """Exact widening of a float32 / bfloat16-bits / float64 matrix to float64 (for the tests' own numpy checks)."""
+    a, code = as_raw(x)
+    if code == BF16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def _p(a, ty):
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+def splitmix64(seed: int, count: int) -> np.ndarray:
+    out = np.empty(count, dtype=np.uint64)
+    _load().pamm_oracle_splitmix64(ctypes.c_uint64(seed), count, _p(out, ctypes.c_uint64))
+    return out
+
+
+def sample(b: int, k: int, seed: int) -> np.ndarray:
+    idx = np.empty(k, dtype=np.int32)
+    rc = _load().pamm_oracle_sample(b, k, ctypes.c_uint64(seed & (2**64 - 1)), _p(idx, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("pamm_oracle_sample: bad arguments")
+    return idx
+
+
+@dataclass
+class Compressed:
+    idx: np.ndarray      # k int32, generator rows in draw order
+    C: np.ndarray        # k x n float64
+    f: np.ndarray        # b int32
+    alpha: np.ndarray    # b float64
+    best: np.ndarray     # b float64, score of the chosen generator
+    second: np.ndarray   # b float64, best score among the other generators (-1 if k == 1)
+    jsecond: np.ndarray  # b int32, generator attaining `second` (-1 if k == 1)
+
+
+def compress(X, k: int, seed: int = 0, idx=None) -> Compressed:
+    """Compress(A, k) at eps = infinity.  `idx` overrides the sampler (caller-chosen generators)."""
+    a, code = as_raw(X)
+    b, n = a.shape
+    idx = sample(b, k, seed) if idx is None else np.ascontiguousarray(idx, dtype=np.int32)
+    assert idx.shape == (k,)
+    C = np.empty((k, n), dtype=np.float64)
+    f = np.empty(b, dtype=np.int32)
+    alpha = np.empty(b, dtype=np.float64)
+    best = np.empty(b, dtype=np.float64)
+    second = np.empty(b, dtype=np.float64)
+    jsecond = np.empty(b, dtype=np.int32)
+    rc = _load().pamm_oracle_compress(
+        a.ctypes.data_as(ctypes.c_void_p), code, b, n, k, _p(idx, ctypes.c_int32),
+        _p(C, ctypes.c_double), _p(f, ctypes.c_int32), _p(alpha, ctypes.c_double),
+        _p(best, ctypes.c_double), _p(second, ctypes.c_double), _p(jsecond, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("pamm_oracle_compress: bad arguments")
+    return Compressed(idx, C, f, alpha, best, second, jsecond)
+
+
+def grad(C, f, alpha, dY):
+    """ApproxMM(C, alpha, f, B): returns (Btilde k x m, Otilde n x m), both float64."""
+    C = np.ascontiguousarray(C, dtype=np.float64)
+    f = np.ascontiguousarray(f, dtype=np.int32)
+    alpha = np.ascontiguousarray(alpha, dtype=np.float64)
+    y, code = as_raw(dY)
+    k, n = C.shape
+    b, m = y.shape
+    assert f.shape == (b,) and alpha.shape == (b,)
+    Bt = np.empty((k, m), dtype=np.float64)
+    O = np.empty((n, m), dtype=np.float64)
+    rc = _load().pamm_oracle_grad(
+        _p(C, ctypes.c_double), _p(f, ctypes.c_int32), _p(alpha, ctypes.c_double),
+        y.ctypes.data_as(ctypes.c_void_p), code, b, n, k, m, _p(Bt, ctypes.c_double), _p(O, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("pamm_oracle_grad: bad arguments")
+    return Bt, O
+
+
+def score(X, i: int, row_j: int) -> float:
+    """s(i, j) for the generator C_j = X[row_j]."""
+    a, code = as_raw(X)
+    return float(_load().pamm_oracle_score(a.ctypes.data_as(ctypes.c_void_p), code, a.shape[1], int(i), int(row_j)))
