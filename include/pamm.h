@@ -1,0 +1,135 @@
+/*
+ * libpamm: Point-Approximate Matrix Multiplication (PAMM) on one AMD MI355X (gfx950).
+ *
+ * The two calls follow the paper's statement of the method (Sec. 3.2): approximate
+ * O = A^T B for A in R^{b x n}, B in R^{b x m} in two stages,
+ *
+ *   pamm_compress   "Compressing A": choose k generator rows C, and for every row A_i
+ *                   the generator f(i) whose line gives the smallest projection residual
+ *                   together with the coefficient alpha_i = <A_i,C_f(i)>/||C_f(i)||^2
+ *                   (Eq. 1, Lemma 1; Alg. 1, procedure Compress, at eps = infinity);
+ *   pamm_grad       "Approximate Matrix Multiplication": Btilde_j = sum_{i: f(i)=j} alpha_i B_i,
+ *                   O~ = C^T Btilde  (Alg. 1, procedure ApproxMM).
+ *
+ * In training, A is the saved input X of the fused Q|K|V projection, B is dY = [dQ|dK|dV]
+ * and O~ is the approximate weight gradient (Alg. 2 and Alg. 3).
+ *
+ * Conventions that hold for every entry point
+ *   - Matrices are row-major and contiguous.  X, C and dY share one element type
+ *     (pamm_dtype); f is int32 and 0-based; alpha is fp32; dW is fp32, n x m
+ *     (the orientation of O = A^T B), and is overwritten, not accumulated into.
+ *   - Unless a parameter is marked "host", pointers are DEVICE pointers on the
+ *     current HIP device, owned by the caller, 16-byte aligned.  The library never
+ *     frees or retains them past the call's enqueued work.
+ *   - Row lengths must keep every row 16-byte aligned: n and m multiples of 8 for
+ *     PAMM_BF16, multiples of 4 for PAMM_F32 (otherwise PAMM_ERR_UNSUPPORTED).
+ *   - b, n, m < 2^31; k <= min(b, 65536).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
+ *     stream).  The calls do not synchronise the stream: outputs are valid once the
+ *     stream has reached the end of the enqueued work.  Scratch memory comes from the
+ *     caller through (ws, ws_bytes), sized by the *_workspace queries; the compute
+ *     calls allocate no device memory.  (pamm_compress keeps a small pinned host ring
+ *     for the sampled indices, created on first use per device.)
+ *   - Errors are return codes.  All argument checks happen on the host before
+ *     anything is enqueued; on a non-OK return nothing was enqueued and no output
+ *     was touched, except PAMM_ERR_DEVICE (a HIP call failed part-way).
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef PAMM_H
+#define PAMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PAMM_OK = 0,
+    PAMM_ERR_INVALID_ARG = 1,   /* null pointer, size out of range, misaligned pointer */
+    PAMM_ERR_UNSUPPORTED = 2,   /* unknown dtype, row length that breaks 16-byte row alignment */
+    PAMM_ERR_WORKSPACE = 3,     /* ws is NULL or ws_bytes is below the matching *_workspace() */
+    PAMM_ERR_DEVICE = 4         /* a HIP runtime call failed */
+} pamm_status;
+
+typedef enum { PAMM_F32 = 0, PAMM_BF16 = 1 } pamm_dtype;   /* element type of X, C and dY */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *pamm_status_string(pamm_status s);
+
+/*
+ * Bytes of device scratch pamm_compress / pamm_compress_idx need for these sizes
+ * (0 if the sizes or dtype are invalid).  Host-only, pure.
+ */
+size_t pamm_compress_workspace(int64_t b, int64_t n, int64_t k, pamm_dtype dt);
+
+/* Bytes of device scratch pamm_grad needs (0 if the sizes or dtype are invalid).  Host-only, pure. */
+size_t pamm_grad_workspace(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt);
+
+/*
+ * Alg. 1, Compress, "sample indices I subset [b] uniformly without replacement, |I| = k".
+ * The paper fixes only the distribution; this library fixes the stream as: splitmix64
+ * seeded with `seed`; draw t = 0..k-1 takes r = t + u where u is uniform on [0, b-t)
+ * by rejection on the 64-bit output (reject x < 2^64 mod (b-t), u = x mod (b-t));
+ * Fisher-Yates exchange of positions t and r of the identity arrangement of [0,b);
+ * idx[t] is the value then at position t.  Generator j is draw j (draw order).
+ * idx_host: HOST pointer to k int32, written by the call.  Pure host function.
+ */
+pamm_status pamm_sample_indices(int64_t b, int64_t k, uint64_t seed, int32_t *idx_host);
+
+/*
+ * Alg. 1, procedure Compress, with eps = infinity (no row dropped, beta = 1).
+ *   X      in   b x n, dtype dt
+ *   seed   in   selects the generators through pamm_sample_indices(b, k, seed)
+ *   C      out  k x n, dtype dt: C_j = X[idx_j], bit copies                     ("C <- A[I,:]")
+ *   f      out  b int32: f(i) = lowest j maximising <X_i,C_j>^2/||C_j||^2       (Lemma 1: argmax |csim|)
+ *   alpha  out  b fp32:  alpha_i = <X_i,C_f(i)>/||C_f(i)||^2                    (Eq. 1)
+ * A generator with zero norm scores 0 and yields alpha 0; a zero row gets f = 0, alpha = 0.
+ * Scores are accumulated in fp32; rows whose two best scores are within 2^-12 relative of
+ * each other are re-decided in fp64, so f agrees with an fp64 evaluation except for
+ * ties below fp64 resolution.
+ */
+pamm_status pamm_compress(const void *X, int64_t b, int64_t n, int64_t k, uint64_t seed, pamm_dtype dt,
+                          void *C, int32_t *f, float *alpha,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The same with caller-chosen generators ("these can be any points close enough to the
+ * points in A", Sec. 3.2; also the hook tests use to bypass the sampler).
+ *   idx_dev  in  DEVICE pointer to k int32 row numbers in [0,b); duplicates are allowed
+ *                (the lowest j of identical generators wins).  Values outside [0,b) are
+ *                clamped into range by the kernel rather than faulting.
+ */
+pamm_status pamm_compress_idx(const void *X, int64_t b, int64_t n, int64_t k, const int32_t *idx_dev,
+                              pamm_dtype dt, void *C, int32_t *f, float *alpha,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Alg. 1, procedure ApproxMM: dW = C^T Btilde with Btilde_j = sum_{i: f(i)=j} alpha_i dY_i.
+ *   C      in   k x n, dtype dt          f      in  b int32 in [0,k)        alpha  in  b fp32
+ *   dY     in   b x m, dtype dt
+ *   dW     out  n x m fp32, overwritten
+ * Rows are grouped by f with a stable counting sort and summed in fp32 in a fixed order, so
+ * the result is bit-reproducible from call to call.  For PAMM_BF16 the contracted rows are
+ * rounded to bf16 once before the C^T Btilde product (fp32 accumulation); for PAMM_F32 the
+ * product is carried out in fp32 throughout.  Entries of f outside [0,k) are clamped into
+ * range by the kernels rather than faulting.
+ */
+pamm_status pamm_grad(const void *C, const int32_t *f, const float *alpha, const void *dY,
+                      int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt,
+                      float *dW, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Test/benchmark hook: only the contraction stage of ApproxMM.
+ *   Btilde out  k x m fp32: Btilde_j = sum_{i: f(i)=j} alpha_i dY_i          (Sec. 3.2, second displayed sum)
+ * Same workspace as pamm_grad.
+ */
+pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
+                          int64_t b, int64_t k, int64_t m, pamm_dtype dt,
+                          float *Btilde, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAMM_H */

@@ -1,0 +1,174 @@
+"""Thin binding over libpamm's C ABI (include/pamm.h): argument marshalling only.
+
+Every step of Compress / ApproxMM runs in the HIP kernels of ``libpamm.so``; torch is used here
+for device memory and the current stream.  There is no fallback: if the library is missing, or no
+MI355X is present when a compute call is made, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpamm.so")
+
+PAMM_OK = 0
+PAMM_ERR_INVALID_ARG, PAMM_ERR_UNSUPPORTED, PAMM_ERR_WORKSPACE, PAMM_ERR_DEVICE = 1, 2, 3, 4
+PAMM_F32, PAMM_BF16 = 0, 1
+
+EXPORTS = [
+    "pamm_status_string", "pamm_compress_workspace", "pamm_grad_workspace", "pamm_sample_indices",
+    "pamm_compress", "pamm_compress_idx", "pamm_grad", "pamm_contract",
+]
+
+
+class PammError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)}")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2506_02939_amd.build` "
+            "(hipcc, gfx950). There is no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, u64, vp, sz, ci = ctypes.c_int64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.pamm_status_string.argtypes = [ci]
+    lib.pamm_status_string.restype = ctypes.c_char_p
+    lib.pamm_compress_workspace.argtypes = [i64, i64, i64, ci]
+    lib.pamm_compress_workspace.restype = sz
+    lib.pamm_grad_workspace.argtypes = [i64, i64, i64, i64, ci]
+    lib.pamm_grad_workspace.restype = sz
+    lib.pamm_sample_indices.argtypes = [i64, i64, u64, vp]
+    lib.pamm_sample_indices.restype = ci
+    lib.pamm_compress.argtypes = [vp, i64, i64, i64, u64, ci, vp, vp, vp, vp, sz, vp]
+    lib.pamm_compress.restype = ci
+    lib.pamm_compress_idx.argtypes = [vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, sz, vp]
+    lib.pamm_compress_idx.restype = ci
+    lib.pamm_grad.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, sz, vp]
+    lib.pamm_grad.restype = ci
+    lib.pamm_contract.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
+    lib.pamm_contract.restype = ci
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.pamm_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != PAMM_OK:
+        raise PammError(status, what)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return PAMM_F32
+    if t.dtype == torch.bfloat16:
+        return PAMM_BF16
+    raise PammError(PAMM_ERR_UNSUPPORTED, f"element type {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (no CPU path exists)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def compress_workspace(b: int, n: int, k: int, dtype: int) -> int:
+    return int(lib.pamm_compress_workspace(b, n, k, dtype))
+
+
+def grad_workspace(b: int, n: int, k: int, m: int, dtype: int) -> int:
+    return int(lib.pamm_grad_workspace(b, n, k, m, dtype))
+
+
+def sample_indices(b: int, k: int, seed: int) -> torch.Tensor:
+    """pamm_sample_indices: k generator rows for (b, seed), a CPU int32 tensor in draw order."""
+    idx = torch.empty(max(k, 0), dtype=torch.int32)
+    _check(lib.pamm_sample_indices(b, k, ctypes.c_uint64(seed & (2**64 - 1)), idx.data_ptr()), "pamm_sample_indices")
+    return idx
+
+
+def _workspace(nbytes: int, device, ws):
+    if ws is None:
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    return ws
+
+
+@dataclass
+class Compressed:
+    C: torch.Tensor       # k x n, element type of X
+    f: torch.Tensor       # b int32
+    alpha: torch.Tensor   # b fp32
+
+
+def compress(X: torch.Tensor, k: int, seed: int = 0, *, idx: torch.Tensor | None = None, out: Compressed | None = None,
+             ws: torch.Tensor | None = None) -> Compressed:
+    """pamm_compress (or pamm_compress_idx when `idx`, a device int32 tensor of k rows, is given)."""
+    b, n = X.shape
+    dt = _dtype_code(X)
+    xp = _dev(X, "X")
+    if out is None:
+        out = Compressed(torch.empty(k, n, dtype=X.dtype, device=X.device),
+                         torch.empty(b, dtype=torch.int32, device=X.device),
+                         torch.empty(b, dtype=torch.float32, device=X.device))
+    nbytes = compress_workspace(b, n, k, dt)
+    if nbytes == 0:
+        # let the library name the problem
+        ws = _workspace(16, X.device, ws)
+    else:
+        ws = _workspace(nbytes, X.device, ws)
+    if idx is None:
+        st = lib.pamm_compress(xp, b, n, k, ctypes.c_uint64(seed & (2**64 - 1)), dt, out.C.data_ptr(), out.f.data_ptr(),
+                               out.alpha.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+        _check(st, "pamm_compress")
+    else:
+        st = lib.pamm_compress_idx(xp, b, n, k, _dev(idx, "idx"), dt, out.C.data_ptr(), out.f.data_ptr(),
+                                   out.alpha.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+        _check(st, "pamm_compress_idx")
+    return out
+
+
+def grad(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, *, out: torch.Tensor | None = None,
+         ws: torch.Tensor | None = None) -> torch.Tensor:
+    """pamm_grad: dW (n x m, fp32) = C^T Btilde."""
+    k, n = C.shape
+    b, m = dY.shape
+    dt = _dtype_code(dY)
+    if C.dtype != dY.dtype:
+        raise PammError(PAMM_ERR_UNSUPPORTED, "C and dY differ in element type")
+    if out is None:
+        out = torch.empty(n, m, dtype=torch.float32, device=dY.device)
+    ws = _workspace(grad_workspace(b, n, k, m, dt), dY.device, ws)
+    st = lib.pamm_grad(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, dt, out.data_ptr(),
+                       ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "pamm_grad")
+    return out
+
+
+def contract(f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, k: int, *, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """pamm_contract: Btilde (k x m, fp32), the contraction stage of ApproxMM alone."""
+    b, m = dY.shape
+    dt = _dtype_code(dY)
+    out = torch.empty(k, m, dtype=torch.float32, device=dY.device)
+    n_any = 8
+    ws = _workspace(grad_workspace(b, n_any, k, m, dt), dY.device, ws)
+    st = lib.pamm_contract(_dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, k, m, dt, out.data_ptr(), ws.data_ptr(),
+                           ws.numel(), _stream())
+    _check(st, "pamm_contract")
+    return out

@@ -1,0 +1,135 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what include/pamm.h declares,
+its sampler agrees with the oracle's, and every argument check fires before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pamm.h")
+
+
+@pytest.fixture(scope="module")
+def pamm():
+    from paper_2506_02939_amd import pamm as p
+
+    return p
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pamm_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree(pamm):
+    declared = _declared_functions()
+    assert declared == sorted(pamm.EXPORTS)
+    for name in declared:
+        assert hasattr(pamm.lib, name), f"libpamm.so does not export {name}"
+
+
+def test_status_strings(pamm):
+    names = {pamm.status_string(i) for i in range(5)}
+    assert names == {"PAMM_OK", "PAMM_ERR_INVALID_ARG", "PAMM_ERR_UNSUPPORTED", "PAMM_ERR_WORKSPACE", "PAMM_ERR_DEVICE"}
+    assert pamm.status_string(99) == "PAMM_ERR_UNKNOWN"
+
+
+@pytest.mark.parametrize("b,k,seed", [(10, 10, 0), (8192, 16, 0), (65536, 128, 0), (16384, 1024, 0), (16384, 32, 12345),
+                                      (2048, 2048, 7), (3, 2, 2**64 - 1), (1, 1, 5)])
+def test_sampler_matches_oracle_stream(pamm, oracle, b, k, seed):
+    """Two independent implementations of the specified sampler (Alg. 1, 'sample indices'): same stream."""
+    got = pamm.sample_indices(b, k, seed).numpy()
+    assert np.array_equal(got, oracle.sample(b, k, seed))
+
+
+def test_sampler_rejects_bad_arguments(pamm):
+    buf = (ctypes.c_int32 * 4)()
+    assert pamm.lib.pamm_sample_indices(4, 5, 0, ctypes.addressof(buf)) == pamm.PAMM_ERR_INVALID_ARG
+    assert pamm.lib.pamm_sample_indices(4, 0, 0, ctypes.addressof(buf)) == pamm.PAMM_ERR_INVALID_ARG
+    assert pamm.lib.pamm_sample_indices(0, 0, 0, ctypes.addressof(buf)) == pamm.PAMM_ERR_INVALID_ARG
+    assert pamm.lib.pamm_sample_indices(4, 2, 0, None) == pamm.PAMM_ERR_INVALID_ARG
+
+
+def test_workspace_queries(pamm):
+    assert pamm.compress_workspace(65536, 2048, 128, pamm.PAMM_BF16) >= 65536 * 32
+    assert pamm.grad_workspace(65536, 2048, 128, 6144, pamm.PAMM_BF16) >= 128 * 6144 * 4
+    # invalid sizes -> 0
+    assert pamm.compress_workspace(16, 64, 17, pamm.PAMM_BF16) == 0        # k > b
+    assert pamm.compress_workspace(16, 60, 4, pamm.PAMM_BF16) == 0         # rows not 16-byte aligned
+    assert pamm.compress_workspace(16, 60, 4, pamm.PAMM_F32) > 0           # 60 floats = 240 bytes is fine
+    assert pamm.compress_workspace(16, 64, 4, 7) == 0                      # unknown dtype
+    assert pamm.grad_workspace(16, 64, 4, 0, pamm.PAMM_F32) == 0
+    assert pamm.grad_workspace(16, 64, 4, 12, pamm.PAMM_BF16) == 0         # m rows not 16-byte aligned
+    # monotone in b
+    assert pamm.compress_workspace(4096, 256, 16, pamm.PAMM_F32) > pamm.compress_workspace(1024, 256, 16, pamm.PAMM_F32)
+
+
+A = 0x10000   # a 16-byte aligned, non-null fake address: the checks below must fail before it is ever touched
+BIG = 1 << 40
+
+
+def _compress(pamm, X=A, b=64, n=64, k=4, seed=0, dt=1, C=A, f=A, alpha=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_compress(X, b, n, k, ctypes.c_uint64(seed), dt, C, f, alpha, ws, ws_bytes, None)
+
+
+def _compress_idx(pamm, X=A, b=64, n=64, k=4, idx=A, dt=1, C=A, f=A, alpha=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_compress_idx(X, b, n, k, idx, dt, C, f, alpha, ws, ws_bytes, None)
+
+
+def _grad(pamm, C=A, f=A, alpha=A, dY=A, b=64, n=64, k=4, m=64, dt=1, dW=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_grad(C, f, alpha, dY, b, n, k, m, dt, dW, ws, ws_bytes, None)
+
+
+def _contract(pamm, f=A, alpha=A, dY=A, b=64, k=4, m=64, dt=1, Bt=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_contract(f, alpha, dY, b, k, m, dt, Bt, ws, ws_bytes, None)
+
+
+def test_compress_argument_checks(pamm):
+    P = pamm
+    for fn in (_compress, _compress_idx):
+        assert fn(P, X=None) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, C=None) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, f=None) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, alpha=None) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, X=A + 4) == P.PAMM_ERR_INVALID_ARG          # misaligned
+        assert fn(P, k=0) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, k=65) == P.PAMM_ERR_INVALID_ARG             # k > b
+        assert fn(P, b=0) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, n=0) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, b=1 << 31, k=4) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, n=60) == P.PAMM_ERR_UNSUPPORTED             # bf16 rows of 120 bytes
+        assert fn(P, dt=5) == P.PAMM_ERR_UNSUPPORTED
+        assert fn(P, b=1 << 20, k=20000) == P.PAMM_ERR_UNSUPPORTED
+        assert fn(P, ws=None) == P.PAMM_ERR_WORKSPACE
+        assert fn(P, ws_bytes=16) == P.PAMM_ERR_WORKSPACE
+        assert fn(P, ws=A + 8) == P.PAMM_ERR_INVALID_ARG
+    assert _compress_idx(P, idx=None) == P.PAMM_ERR_INVALID_ARG
+
+
+def test_grad_argument_checks(pamm):
+    P = pamm
+    assert _grad(P, C=None) == P.PAMM_ERR_INVALID_ARG
+    assert _grad(P, dW=None) == P.PAMM_ERR_INVALID_ARG
+    assert _grad(P, dY=A + 2) == P.PAMM_ERR_INVALID_ARG
+    assert _grad(P, m=0) == P.PAMM_ERR_INVALID_ARG
+    assert _grad(P, k=65) == P.PAMM_ERR_INVALID_ARG
+    assert _grad(P, m=12) == P.PAMM_ERR_UNSUPPORTED
+    assert _grad(P, dt=-1) == P.PAMM_ERR_UNSUPPORTED
+    assert _grad(P, ws=None) == P.PAMM_ERR_WORKSPACE
+    assert _grad(P, ws_bytes=1024) == P.PAMM_ERR_WORKSPACE
+    for fn_kw in ("f", "alpha", "dY", "Bt"):
+        assert _contract(P, **{fn_kw: None}) == P.PAMM_ERR_INVALID_ARG
+    assert _contract(P, m=4, dt=1) == P.PAMM_ERR_UNSUPPORTED
+    assert _contract(P, ws_bytes=64) == P.PAMM_ERR_WORKSPACE
+    assert _contract(P, k=0) == P.PAMM_ERR_INVALID_ARG
+
+
+def test_binding_refuses_cpu_tensors(pamm):
+    import torch
+
+    X = torch.zeros(64, 64, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        pamm.compress(X, 4)
