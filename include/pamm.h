@@ -23,7 +23,7 @@
  *     frees or retains them past the call's enqueued work.
  *   - Row lengths must keep every row 16-byte aligned: n and m multiples of 8 for
  *     PAMM_BF16, multiples of 4 for PAMM_F32 (otherwise PAMM_ERR_UNSUPPORTED).
- *   - b, n, m < 2^31; k <= min(b, 65536).
+ *   - b, n, m < 2^31; k <= min(b, 16384) (larger k: PAMM_ERR_UNSUPPORTED).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
  *     stream).  The calls do not synchronise the stream: outputs are valid once the
  *     stream has reached the end of the enqueued work.  Scratch memory comes from the
@@ -128,6 +128,19 @@ pamm_status pamm_grad(const void *C, const int32_t *f, const float *alpha, const
 pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
                           int64_t b, int64_t k, int64_t m, pamm_dtype dt,
                           float *Btilde, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Per-kernel timing for benchmarks (the paper reports its own cost per operation in App. F, Tables 6-7).
+ * Between pamm_profile_begin() and pamm_profile_end() every kernel the library launches is bracketed by
+ * a pair of HIP events on its launch stream (events are created per launch: not for use on a hot path).
+ * pamm_profile_end waits for those events and returns, per kernel id in [0, PAMM_NUM_KERNELS), the summed
+ * elapsed milliseconds and the number of launches; both arrays are HOST pointers of PAMM_NUM_KERNELS
+ * entries.  pamm_kernel_name gives the name of a kernel id ("" if out of range).  Process-wide state.
+ */
+#define PAMM_NUM_KERNELS 7
+pamm_status pamm_profile_begin(void);
+pamm_status pamm_profile_end(double *ms_total, int64_t *launches);
+const char *pamm_kernel_name(int id);
 
 #ifdef __cplusplus
 }

@@ -2,8 +2,13 @@
 #include <unordered_map>
 
 #include "pamm_plan.h"
+#include "pamm_profile.h"
 
 using namespace pamm;
+
+namespace pamm {
+Profiler g_profiler;
+}
 
 extern "C" const char* pamm_status_string(pamm_status s) {
     switch (s) {
@@ -67,4 +72,34 @@ extern "C" pamm_status pamm_sample_indices(int64_t b, int64_t k, uint64_t seed, 
         idx_host[t] = int32_t(vr);
     }
     return PAMM_OK;
+}
+
+extern "C" const char* pamm_kernel_name(int id) {
+    static const char* names[kNumKernels] = {"k_gather", "k_score", "k_finalize", "k_group", "k_contract", "k_ctb", "k_piece_sum"};
+    return (id >= 0 && id < kNumKernels) ? names[id] : "";
+}
+
+extern "C" pamm_status pamm_profile_begin(void) {
+    std::lock_guard<std::mutex> lock(g_profiler.mu);
+    for (auto& sp : g_profiler.spans) { (void)hipEventDestroy(sp.start); (void)hipEventDestroy(sp.stop); }
+    g_profiler.spans.clear();
+    g_profiler.on = true;
+    return PAMM_OK;
+}
+
+extern "C" pamm_status pamm_profile_end(double* ms_total, int64_t* launches) {
+    if (!ms_total || !launches) return PAMM_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_profiler.mu);
+    g_profiler.on = false;
+    for (int i = 0; i < kNumKernels; ++i) { ms_total[i] = 0.0; launches[i] = 0; }
+    pamm_status st = PAMM_OK;
+    for (auto& sp : g_profiler.spans) {
+        float ms = 0.f;
+        if (hipEventSynchronize(sp.stop) != hipSuccess || hipEventElapsedTime(&ms, sp.start, sp.stop) != hipSuccess) st = PAMM_ERR_DEVICE;
+        else { ms_total[sp.id] += double(ms); launches[sp.id] += 1; }
+        (void)hipEventDestroy(sp.start);
+        (void)hipEventDestroy(sp.stop);
+    }
+    g_profiler.spans.clear();
+    return st;
 }

@@ -13,6 +13,7 @@
 
 #include "pamm_device.h"
 #include "pamm_plan.h"
+#include "pamm_profile.h"
 
 namespace pamm {
 
@@ -369,10 +370,19 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
     unsigned long long* hash = reinterpret_cast<unsigned long long*>(ws + pl.off_hash);
     uint4* cand = reinterpret_cast<uint4*>(ws + pl.off_cand);
 
-    hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const uint4*)X, idx_src, b, nch, (uint4*)C, idx, inv, cn2, hash);
-    launch_score<TR>(pl, X, C, inv, b, nch, k, cand, s);
-    hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const uint4*)X, (const uint4*)C, inv, cn2,
-                       hash, cand, b, nch, k, pl.ncb, f, alpha);
+    {
+        ScopedSpan span(kGather, s);
+        hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const uint4*)X, idx_src, b, nch, (uint4*)C, idx, inv, cn2, hash);
+    }
+    {
+        ScopedSpan span(kScore, s);
+        launch_score<TR>(pl, X, C, inv, b, nch, k, cand, s);
+    }
+    {
+        ScopedSpan span(kFinalize, s);
+        hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const uint4*)X, (const uint4*)C, inv, cn2,
+                           hash, cand, b, nch, k, pl.ncb, f, alpha);
+    }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
 

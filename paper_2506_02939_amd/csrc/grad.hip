@@ -11,6 +11,7 @@
 
 #include "pamm_device.h"
 #include "pamm_plan.h"
+#include "pamm_profile.h"
 
 namespace pamm {
 
@@ -381,11 +382,17 @@ static GradBuffers carve(const GradPlan& pl, char* ws) {
 template <typename TR>
 static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, const int32_t* f, const float* alpha, const void* dY,
                                   int b, int k, int m, hipStream_t s) {
-    hipLaunchKernelGGL(k_group, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, int(pl.nslots), g.perm, g.alpha_s, g.row0,
-                       g.len, g.sbase, g.snum);
+    {
+        ScopedSpan span(kGroup, s);
+        hipLaunchKernelGGL(k_group, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, int(pl.nslots), g.perm, g.alpha_s,
+                           g.row0, g.len, g.sbase, g.snum);
+    }
     const int mch = m / TR::kPerChunk;
-    hipLaunchKernelGGL((k_contract<TR>), dim3((unsigned)(pl.nslots * pl.col_groups)), dim3(64), 0, s, (const uint4*)dY, g.perm,
-                       g.alpha_s, g.row0, g.len, mch, m, pl.col_groups, g.partial);
+    {
+        ScopedSpan span(kContract, s);
+        hipLaunchKernelGGL((k_contract<TR>), dim3((unsigned)(pl.nslots * pl.col_groups)), dim3(64), 0, s, (const uint4*)dY, g.perm,
+                           g.alpha_s, g.row0, g.len, mch, m, pl.col_groups, g.partial);
+    }
 }
 
 }  // namespace pamm
@@ -406,8 +413,11 @@ extern "C" pamm_status pamm_contract(const int32_t* f, const float* alpha, const
     GradBuffers g = carve(pl, (char*)ws);
     if (dt == PAMM_BF16) launch_group_contract<Bf16>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
     else launch_group_contract<F32>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-    hipLaunchKernelGGL(k_piece_sum, dim3((unsigned)((m / 4 + 255) / 256), (unsigned)k), dim3(256), 0, s, g.partial, g.sbase, g.snum,
-                       int(m), Btilde);
+    {
+        ScopedSpan span(kPieceSum, s);
+        hipLaunchKernelGGL(k_piece_sum, dim3((unsigned)((m / 4 + 255) / 256), (unsigned)k), dim3(256), 0, s, g.partial, g.sbase,
+                           g.snum, int(m), Btilde);
+    }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
 
@@ -426,10 +436,12 @@ extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* a
     const int tiles_n = int((n + 127) / 128), tiles_m = int((m + 127) / 128);
     if (dt == PAMM_BF16) {
         launch_group_contract<Bf16>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
+        ScopedSpan span(kCtb, s);
         hipLaunchKernelGGL((k_ctb<Bf16>), dim3((unsigned)(tiles_n * tiles_m)), dim3(256), 0, s, (const uint4*)C, g.partial, g.sbase,
                            g.snum, int(n), int(m), int(k), tiles_m, dW);
     } else {
         launch_group_contract<F32>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
+        ScopedSpan span(kCtb, s);
         hipLaunchKernelGGL((k_ctb<F32>), dim3((unsigned)(tiles_n * tiles_m)), dim3(256), 0, s, (const uint4*)C, g.partial, g.sbase,
                            g.snum, int(n), int(m), int(k), tiles_m, dW);
     }

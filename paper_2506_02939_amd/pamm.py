@@ -22,7 +22,9 @@ PAMM_F32, PAMM_BF16 = 0, 1
 EXPORTS = [
     "pamm_status_string", "pamm_compress_workspace", "pamm_grad_workspace", "pamm_sample_indices",
     "pamm_compress", "pamm_compress_idx", "pamm_grad", "pamm_contract",
+    "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
 ]
+NUM_KERNELS = 7
 
 
 class PammError(RuntimeError):
@@ -54,6 +56,12 @@ def _load() -> ctypes.CDLL:
     lib.pamm_grad.restype = ci
     lib.pamm_contract.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_contract.restype = ci
+    lib.pamm_profile_begin.argtypes = []
+    lib.pamm_profile_begin.restype = ci
+    lib.pamm_profile_end.argtypes = [vp, vp]
+    lib.pamm_profile_end.restype = ci
+    lib.pamm_kernel_name.argtypes = [ci]
+    lib.pamm_kernel_name.restype = ctypes.c_char_p
     return lib
 
 
@@ -172,3 +180,15 @@ def contract(f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, k: int, *, 
                            ws.numel(), _stream())
     _check(st, "pamm_contract")
     return out
+
+
+def profile_begin() -> None:
+    _check(lib.pamm_profile_begin(), "pamm_profile_begin")
+
+
+def profile_end() -> dict:
+    """{kernel name: (total milliseconds, launches)} for the kernels launched since profile_begin()."""
+    ms = (ctypes.c_double * NUM_KERNELS)()
+    n = (ctypes.c_int64 * NUM_KERNELS)()
+    _check(lib.pamm_profile_end(ctypes.addressof(ms), ctypes.addressof(n)), "pamm_profile_end")
+    return {lib.pamm_kernel_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS) if n[i] > 0}
