@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llama1b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (the reference reading for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -147,6 +149,15 @@ def main() -> int:
         "roofline": roofline,
         "kernels": kernels,
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calibrate_copy_bytes"] = 1 << 30
+        del src, dst
 
     if not args.no_exact_gemm:
         Xt = X.t().contiguous()

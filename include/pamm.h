@@ -137,7 +137,7 @@ pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
  * elapsed milliseconds and the number of launches; both arrays are HOST pointers of PAMM_NUM_KERNELS
  * entries.  pamm_kernel_name gives the name of a kernel id ("" if out of range).  Process-wide state.
  */
-#define PAMM_NUM_KERNELS 7
+#define PAMM_NUM_KERNELS 8
 pamm_status pamm_profile_begin(void);
 pamm_status pamm_profile_end(double *ms_total, int64_t *launches);
 const char *pamm_kernel_name(int id);

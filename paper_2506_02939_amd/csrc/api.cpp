@@ -75,7 +75,7 @@ extern "C" pamm_status pamm_sample_indices(int64_t b, int64_t k, uint64_t seed, 
 }
 
 extern "C" const char* pamm_kernel_name(int id) {
-    static const char* names[kNumKernels] = {"k_gather", "k_score", "k_finalize", "k_group", "k_contract", "k_ctb", "k_piece_sum"};
+    static const char* names[kNumKernels] = {"k_gather", "k_score", "k_finalize", "k_group", "k_contract", "k_prep", "k_ctb", "k_piece_sum"};
     return (id >= 0 && id < kNumKernels) ? names[id] : "";
 }
 

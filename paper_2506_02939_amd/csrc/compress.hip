@@ -64,18 +64,18 @@ struct Best {
 // ------------------------------------------------------------------------------------------------
 // k_gather: one workgroup per generator.
 template <typename TR>
-__global__ __launch_bounds__(256) void k_gather(const uint4* __restrict__ X, const int32_t* __restrict__ idx_in, int b, int nch,
-                                                uint4* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
+__global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, const int32_t* __restrict__ idx_in, int b, int nch,
+                                                u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
                                                 double* __restrict__ cn2, unsigned long long* __restrict__ hash) {
     const int j = blockIdx.x;
     int src = idx_in[j];
     src = src < 0 ? 0 : (src >= b ? b - 1 : src);
-    const uint4* xr = X + size_t(src) * nch;
-    uint4* cr = C + size_t(j) * nch;
+    const u32x4_t* xr = X + size_t(src) * nch;
+    u32x4_t* cr = C + size_t(j) * nch;
     double acc = 0.0;
     unsigned long long h = 0;
     for (int c = threadIdx.x; c < nch; c += 256) {
-        uint4 v = xr[c];
+        u32x4_t v = xr[c];
         cr[c] = v;
         float e[TR::kPerChunk];
         TR::unpack(v, e);
@@ -117,17 +117,17 @@ __global__ __launch_bounds__(256) void k_gather(const uint4* __restrict__ X, con
 //
 // C is staged through LDS in stages of 64/TG chunks per generator (32 KiB per stage), double
 // buffered: global loads of stage s+1 are in flight while stage s is consumed.
-template <typename TR, int TG, int TT>
-__global__ __launch_bounds__(256) void k_score(const uint4* __restrict__ X, const uint4* __restrict__ C,
+template <typename TR, int TG, int TT, bool ALIGNED>
+__global__ __launch_bounds__(256) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
                                                const float* __restrict__ inv, int b, int nch, int k, int ncb,
-                                               uint4* __restrict__ cand) {
+                                               u32x4_t* __restrict__ cand) {
     constexpr int GB = 32 * TG;          // generators per column block
     constexpr int SS = 8 / TG;           // super-steps per stage
     constexpr int CPS = 8 * SS;          // chunks per generator per stage
     constexpr int RS = CPS + 1;          // LDS row stride in chunks (odd: conflict-free 16-byte reads down a column)
     constexpr int LOADS = GB * CPS / 256;   // = 8 chunks per thread per stage
 
-    __shared__ uint4 lds_c[2][GB * RS];
+    __shared__ u32x4_t lds_c[2][GB * RS];
     __shared__ float lds_inv[GB];
 
     const int tid = threadIdx.x;
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void k_score(const uint4* __restrict__ X, cons
 
     // token rows of this lane (clamped: rows past the end are computed on a valid row and never stored)
     const int row_base = rt * (128 * TT) + wave * (32 * TT);
-    const uint4* xrow[TT];
+    const u32x4_t* xrow[TT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         int row = row_base + 32 * tt + r;
@@ -160,16 +160,19 @@ __global__ __launch_bounds__(256) void k_score(const uint4* __restrict__ X, cons
             for (int i = 0; i < 16; ++i) acc[a][t][i] = 0.f;
 
     const int nstages = (nch + CPS - 1) / CPS;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    const int nss = (nch + 7) / 8;               // super-steps
 
-    uint4 creg[LOADS];
+    u32x4_t creg[LOADS];
     auto load_c = [&](int stage) {
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             int q = tid + 256 * i;
             int row = q / CPS, cc = q % CPS;
-            int j = gen0 + row, c = stage * CPS + cc;
-            creg[i] = (j < k && c < nch) ? C[size_t(j) * nch + c] : zero4;
+            const int j = gen0 + row, c = stage * CPS + cc;
+            // Clamped addresses, no guard and no mask: a guarded load costs a branch per chunk, and a mask makes
+            // the compiler wait for the load where it is issued.  Rows past the last generator are ignored by
+            // the epilogue; chunks past the end of a row meet zero chunks of X.
+            creg[i] = C[size_t(min(j, k - 1)) * nch + min(c, nch - 1)];
         }
     };
     auto store_c = [&](int buf) {
@@ -179,47 +182,72 @@ __global__ __launch_bounds__(256) void k_score(const uint4* __restrict__ X, cons
             lds_c[buf][(q / CPS) * RS + (q % CPS)] = creg[i];
         }
     };
-    uint4 xcur[TT][4], xnext[TT][4];
-    auto load_x = [&](uint4 (&dst)[TT][4], int sstep) {
+    // X ring: D super-steps of this lane's chunks live in registers; loads run D-1 super-steps ahead of the
+    // MFMAs so that every wave keeps (D-1) * TT * 4 KiB of X in flight.
+    constexpr int D = (TG * TT >= 16) ? 2 : 4;
+    constexpr int UN = SS > D ? SS : D;          // super-steps per unrolled body: a multiple of SS and of D
+    u32x4_t xr[D][TT][4];
+    auto load_x = [&](u32x4_t (&dst)[TT][4], int sstep) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                int c = sstep * 8 + 4 * g + u;
-                dst[tt][u] = c < nch ? xrow[tt][c] : zero4;
+                if (ALIGNED) {        // rows are whole super-steps: clamp the super-step, nothing to mask
+#if defined(PAMM_DBG_NOX)
+                    dst[tt][u] = u32x4_t{uint32_t(sstep), 1u, 2u, 3u};
+#else
+                    dst[tt][u] = xrow[tt][min(sstep, nss - 1) * 8 + 4 * g + u];
+#endif
+                } else {
+                    const int c = sstep * 8 + 4 * g + u;
+                    const uint32_t keep = c < nch ? 0xffffffffu : 0u;
+                    dst[tt][u] = xrow[tt][min(c, nch - 1)] & keep;
+                }
             }
     };
 
     load_c(0);
-    load_x(xcur, 0);
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
     store_c(0);
     __syncthreads();
 
-    int buf = 0;
-    for (int st = 0; st < nstages; ++st) {
-        const bool more = st + 1 < nstages;
-        if (more) load_c(st + 1);
+    const int nbody = (nss + UN - 1) / UN;
+    int buf = 0, stage = 0;
+    for (int bi = 0; bi < nbody; ++bi) {
 #pragma unroll
-        for (int ss = 0; ss < SS; ++ss) {
-            load_x(xnext, st * SS + ss + 1);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                uint4 a[TG];
-#pragma unroll
-                for (int tg = 0; tg < TG; ++tg) a[tg] = lds_c[buf][(32 * tg + r) * RS + ss * 8 + 4 * g + u];
-#pragma unroll
-                for (int tg = 0; tg < TG; ++tg)
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) TR::mma(a[tg], xcur[tt][u], acc[tg][tt]);
+        for (int p = 0; p < UN; ++p) {
+            const int gs = bi * UN + p;                      // super-step
+            if (p % SS == 0) {                               // a stage of C begins
+                stage = gs / SS;
+                if (stage + 1 < nstages) load_c(stage + 1);
             }
+            load_x(xr[(p + D - 1) % D], gs + D - 1);
+            if (gs < nss) {                                  // uniform; only false in the tail of the last body
+                const u32x4_t* cbuf = lds_c[buf];
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
+                for (int u = 0; u < 4; ++u) {
+                    u32x4_t a[TG];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) xcur[tt][u] = xnext[tt][u];
+                    for (int tg = 0; tg < TG; ++tg) a[tg] = cbuf[(32 * tg + r) * RS + (p % SS) * 8 + 4 * g + u];
+#pragma unroll
+                    for (int tg = 0; tg < TG; ++tg)
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) {
+#if defined(PAMM_DBG_NOMMA)
+                            acc[tg][tt][0] += __uint_as_float(a[tg].x ^ xr[p % D][tt][u].x);
+#else
+                            TR::mma(a[tg], xr[p % D][tt][u], acc[tg][tt]);
+#endif
+                        }
+                }
+            }
+            if (p % SS == SS - 1) {                          // the stage ends: publish the next one
+                if (stage + 1 < nstages) store_c(buf ^ 1);
+                __syncthreads();
+                buf ^= 1;
+            }
         }
-        if (more) store_c(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
     }
 
     // epilogue: D layout of the 32x32 MFMA: register i of lane (r,g) is generator 8*(i/4)+4*g+(i%4), token r
@@ -245,9 +273,9 @@ __global__ __launch_bounds__(256) void k_score(const uint4* __restrict__ X, cons
         best.merge(o);
         int row = row_base + 32 * tt + r;
         if (g == 0 && row < b) {
-            uint4* dst = cand + (size_t(row) * ncb + cb) * 2;
-            dst[0] = make_uint4(__float_as_uint(best.s1), uint32_t(best.j1), __float_as_uint(best.d1), uint32_t(best.jt));
-            dst[1] = make_uint4(__float_as_uint(best.s2), uint32_t(best.j2), __float_as_uint(best.s3), 0u);
+            u32x4_t* dst = cand + (size_t(row) * ncb + cb) * 2;
+            dst[0] = u32x4_t{__float_as_uint(best.s1), uint32_t(best.j1), __float_as_uint(best.d1), uint32_t(best.jt)};
+            dst[1] = u32x4_t{__float_as_uint(best.s2), uint32_t(best.j2), __float_as_uint(best.s3), 0u};
         }
     }
 }
@@ -255,7 +283,7 @@ __global__ __launch_bounds__(256) void k_score(const uint4* __restrict__ X, cons
 // ------------------------------------------------------------------------------------------------
 // k_finalize: one thread per token.
 template <typename TR>
-__device__ __forceinline__ double wave_dot(const uint4* __restrict__ x, const uint4* __restrict__ c, int nch, int lane) {
+__device__ __forceinline__ double wave_dot(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ c, int nch, int lane) {
     double acc = 0.0;
     for (int q = lane; q < nch; q += kWave) {
         float a[TR::kPerChunk], bq[TR::kPerChunk];
@@ -268,10 +296,10 @@ __device__ __forceinline__ double wave_dot(const uint4* __restrict__ x, const ui
 }
 
 template <typename TR>
-__global__ __launch_bounds__(256) void k_finalize(const uint4* __restrict__ X, const uint4* __restrict__ C,
+__global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
                                                   const float* __restrict__ inv, const double* __restrict__ cn2,
                                                   const unsigned long long* __restrict__ hash,
-                                                  const uint4* __restrict__ cand, int b, int nch, int k, int ncb,
+                                                  const u32x4_t* __restrict__ cand, int b, int nch, int k, int ncb,
                                                   int32_t* __restrict__ f, float* __restrict__ alpha) {
     const int row = blockIdx.x * 256 + threadIdx.x;
     const int lane = threadIdx.x & 63;
@@ -280,8 +308,8 @@ __global__ __launch_bounds__(256) void k_finalize(const uint4* __restrict__ X, c
     st.init();
     if (valid) {
         for (int cb = 0; cb < ncb; ++cb) {
-            const uint4* src = cand + (size_t(row) * ncb + cb) * 2;
-            uint4 p = src[0], q = src[1];
+            const u32x4_t* src = cand + (size_t(row) * ncb + cb) * 2;
+            u32x4_t p = src[0], q = src[1];
             Best o;
             o.s1 = __uint_as_float(p.x); o.j1 = int(p.y); o.d1 = __uint_as_float(p.z); o.jt = int(p.w);
             o.s2 = __uint_as_float(q.x); o.j2 = int(q.y); o.s3 = __uint_as_float(q.z);
@@ -309,7 +337,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint4* __restrict__ X, c
         pending &= pending - 1;
         const int rrow = __shfl(row, L), rmode = __shfl(mode, L);
         const int ja = __shfl(st.j1, L), jb = __shfl(other, L);
-        const uint4* xr = X + size_t(rrow) * nch;
+        const u32x4_t* xr = X + size_t(rrow) * nch;
         double bs = -1.0, bd = 0.0, bc = 1.0;
         int bj = 0;
         auto eval = [&](int j) {
@@ -341,17 +369,19 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 template <typename TR, int TG>
 static void launch_score_tt(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
-                            uint4* cand, hipStream_t s) {
+                            u32x4_t* cand, hipStream_t s) {
     dim3 grid((unsigned)(pl.row_tiles * pl.ncb));
-    if (pl.tt == 2)
-        hipLaunchKernelGGL((k_score<TR, TG, 2>), grid, dim3(256), 0, s, (const uint4*)X, (const uint4*)C, inv, b, nch, k, pl.ncb, cand);
-    else
-        hipLaunchKernelGGL((k_score<TR, TG, 1>), grid, dim3(256), 0, s, (const uint4*)X, (const uint4*)C, inv, b, nch, k, pl.ncb, cand);
+    const bool aligned = nch % 8 == 0;      // every row is a whole number of 128-byte super-steps
+#define PAMM_LAUNCH_SCORE(TTV, AL) \
+    hipLaunchKernelGGL((k_score<TR, TG, TTV, AL>), grid, dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv, b, nch, k, pl.ncb, cand)
+    if (pl.tt == 2) { if (aligned) PAMM_LAUNCH_SCORE(2, true); else PAMM_LAUNCH_SCORE(2, false); }
+    else            { if (aligned) PAMM_LAUNCH_SCORE(1, true); else PAMM_LAUNCH_SCORE(1, false); }
+#undef PAMM_LAUNCH_SCORE
 }
 
 template <typename TR>
 static void launch_score(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
-                         uint4* cand, hipStream_t s) {
+                         u32x4_t* cand, hipStream_t s) {
     switch (pl.tg) {
         case 1: launch_score_tt<TR, 1>(pl, X, C, inv, b, nch, k, cand, s); break;
         case 2: launch_score_tt<TR, 2>(pl, X, C, inv, b, nch, k, cand, s); break;
@@ -368,11 +398,11 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
     float* inv = reinterpret_cast<float*>(ws + pl.off_inv);
     double* cn2 = reinterpret_cast<double*>(ws + pl.off_cn2);
     unsigned long long* hash = reinterpret_cast<unsigned long long*>(ws + pl.off_hash);
-    uint4* cand = reinterpret_cast<uint4*>(ws + pl.off_cand);
+    u32x4_t* cand = reinterpret_cast<u32x4_t*>(ws + pl.off_cand);
 
     {
         ScopedSpan span(kGather, s);
-        hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const uint4*)X, idx_src, b, nch, (uint4*)C, idx, inv, cn2, hash);
+        hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_src, b, nch, (u32x4_t*)C, idx, inv, cn2, hash);
     }
     {
         ScopedSpan span(kScore, s);
@@ -380,7 +410,7 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
     }
     {
         ScopedSpan span(kFinalize, s);
-        hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const uint4*)X, (const uint4*)C, inv, cn2,
+        hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv, cn2,
                            hash, cand, b, nch, k, pl.ncb, f, alpha);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;

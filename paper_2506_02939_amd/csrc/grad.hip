@@ -19,8 +19,11 @@ namespace pamm {
 // k_group.  grid = k, 1024 threads.  Every workgroup reads all of f twice (f is b int32: it stays in
 // L2): pass 1 counts rows with key < j (start of generator j's list) and key == j per wave, pass 2
 // compacts the matching row numbers with ballots, which keeps them in increasing order.
-// Slot table: generator j owns slots [seg_start_j / P + j, ... + ceil(count_j / P)); these ranges are
-// disjoint and fit in floor(b/P) + k slots; slots between two generators' ranges are marked empty here.
+//
+// The sorted list (perm, alpha_s, key_s) is later cut into chunks of P consecutive positions; a
+// "piece" is a maximal run of one generator inside one chunk and is numbered chunk + generator.
+// Piece numbers are unique, increase along the list and stay below ceil(b/P) + k.  Generator j owns
+// the pieces [seg_start_j / P + j, (seg_end_j - 1) / P + j].
 __device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, int i0, int b, int k, int (&key)[4]) {
     if (i0 + 3 < b) {
         int4 v = *reinterpret_cast<const int4*>(f + i0);
@@ -39,9 +42,9 @@ __device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, int i0,
 }
 
 __global__ __launch_bounds__(1024) void k_group(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                int P, int nslots, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
-                                                int32_t* __restrict__ slot_row0, int32_t* __restrict__ slot_len,
-                                                int32_t* __restrict__ sbase, int32_t* __restrict__ snum) {
+                                                int P, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
+                                                int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
+                                                int32_t* __restrict__ snum) {
     const int j = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const long long per_wave = (((long long)b + 15) / 16 + 255) / 256 * 256;
@@ -69,123 +72,138 @@ __global__ __launch_bounds__(1024) void k_group(const int32_t* __restrict__ f, c
         count += s_eq[w];
     }
 
-    int pos = seg_start + woff;
-    const unsigned long long below = (1ull << lane) - 1ull;
-    for (int base = r0; base < r1; base += 256) {
-        const int i0 = base + 4 * lane;
-        int key[4];
-        load_keys(f, i0, b, k, key);
-        int before = 0, total = 0;
-        bool hit[4];
+    if (s_eq[wave] > 0) {                  // wave-uniform: most waves hold no row of this generator when k is large
+        int pos = seg_start + woff;
+        const unsigned long long below = (1ull << lane) - 1ull;
+        for (int base = r0; base < r1; base += 256) {
+            const int i0 = base + 4 * lane;
+            int key[4];
+            load_keys(f, i0, b, k, key);
+            int before = 0, total = 0;
+            bool hit[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            hit[c] = key[c] == j;
-            unsigned long long m = __ballot(hit[c]);
-            before += __popcll(m & below);
-            total += __popcll(m);
-        }
-        int within = 0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (hit[c]) {
-                perm[pos + before + within] = i0 + c;
-                alpha_s[pos + before + within] = alpha[i0 + c];
-                ++within;
+            for (int c = 0; c < 4; ++c) {
+                hit[c] = key[c] == j;
+                unsigned long long m = __ballot(hit[c]);
+                before += __popcll(m & below);
+                total += __popcll(m);
             }
+            int within = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (hit[c]) {
+                    perm[pos + before + within] = i0 + c;
+                    alpha_s[pos + before + within] = alpha[i0 + c];
+                    key_s[pos + before + within] = j;
+                    ++within;
+                }
+            }
+            pos += total;
         }
-        pos += total;
     }
-
-    const int base_j = seg_start / P + j;
-    const int np = (count + P - 1) / P;
-    const int next_base = (j == k - 1) ? nslots : (seg_start + count) / P + j + 1;
-    for (int q = tid; q < next_base - base_j; q += 1024) {
-        const bool live = q < np;
-        slot_row0[base_j + q] = live ? seg_start + q * P : 0;
-        slot_len[base_j + q] = live ? min(P, count - q * P) : 0;
+    if (tid == 0) {
+        sbase[j] = seg_start / P + j;
+        snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
     }
-    if (tid == 0) { sbase[j] = base_j; snum[j] = np; }
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_contract.  One wave per (slot, 512-column group); lane covers 8 consecutive columns.
+// k_contract.  One wave per (chunk of P list positions, 512-column group); lane covers 8 consecutive
+// columns.  Every wave moves the same number of bytes, whatever the sizes of the generators' lists.
+// When the generator changes inside a chunk the running sums are written out as one piece and reset.
 template <typename TR> struct RowLoad;
 
 template <> struct RowLoad<Bf16> {      // 8 columns = one 16-byte chunk
-    uint4 v;
-    __device__ __forceinline__ void load(const uint4* __restrict__ rowp, int ch, int mch) { v = ch < mch ? rowp[ch] : make_uint4(0, 0, 0, 0); }
+    u32x4_t v;
+    static constexpr int kGroup = 8;     // rows fetched per group
+    __device__ __forceinline__ void load(const u32x4_t* __restrict__ rowp, int ch, int) { v = rowp[ch]; }
     __device__ __forceinline__ void fma(float a, float (&acc)[8]) const {
         float e[8];
         Bf16::unpack(v, e);
 #pragma unroll
         for (int q = 0; q < 8; ++q) acc[q] = fmaf(a, e[q], acc[q]);
     }
-    static __device__ __forceinline__ int chunk_of(int grp, int lane) { return grp * 64 + lane; }
-    static __device__ __forceinline__ bool any(int ch, int mch) { return ch < mch; }
-    static __device__ __forceinline__ bool second_half(int, int) { return true; }
+    // chunk index of this lane, clamped into the row (lanes past the last column load valid data and store nothing)
+    static __device__ __forceinline__ int chunk_of(int grp, int lane, int mch) { return min(grp * 64 + lane, mch - 1); }
 };
 
 template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
-    uint4 v0, v1;
-    __device__ __forceinline__ void load(const uint4* __restrict__ rowp, int ch, int mch) {
-        v0 = ch < mch ? rowp[ch] : make_uint4(0, 0, 0, 0);
-        v1 = ch + 1 < mch ? rowp[ch + 1] : make_uint4(0, 0, 0, 0);
-    }
+    u32x4_t v0, v1;
+    static constexpr int kGroup = 4;
+    __device__ __forceinline__ void load(const u32x4_t* __restrict__ rowp, int ch, int mch) { v0 = rowp[ch]; v1 = rowp[min(ch + 1, mch - 1)]; }
     __device__ __forceinline__ void fma(float a, float (&acc)[8]) const {
         acc[0] = fmaf(a, __uint_as_float(v0.x), acc[0]); acc[1] = fmaf(a, __uint_as_float(v0.y), acc[1]);
         acc[2] = fmaf(a, __uint_as_float(v0.z), acc[2]); acc[3] = fmaf(a, __uint_as_float(v0.w), acc[3]);
         acc[4] = fmaf(a, __uint_as_float(v1.x), acc[4]); acc[5] = fmaf(a, __uint_as_float(v1.y), acc[5]);
         acc[6] = fmaf(a, __uint_as_float(v1.z), acc[6]); acc[7] = fmaf(a, __uint_as_float(v1.w), acc[7]);
     }
-    static __device__ __forceinline__ int chunk_of(int grp, int lane) { return 2 * (grp * 64 + lane); }
-    static __device__ __forceinline__ bool any(int ch, int mch) { return ch < mch; }
-    static __device__ __forceinline__ bool second_half(int ch, int mch) { return ch + 1 < mch; }
+    static __device__ __forceinline__ int chunk_of(int grp, int lane, int mch) { return min(2 * (grp * 64 + lane), mch - 1); }
 };
 
 template <typename TR>
-__global__ __launch_bounds__(64) void k_contract(const uint4* __restrict__ dY, const int32_t* __restrict__ perm,
-                                                 const float* __restrict__ alpha_s, const int32_t* __restrict__ slot_row0,
-                                                 const int32_t* __restrict__ slot_len, int mch, int m, int cg,
-                                                 float* __restrict__ partial) {
-    const int slot = blockIdx.x / cg, grp = blockIdx.x % cg;
-    const int len = slot_len[slot];
-    if (len == 0) return;
-    const int row0 = slot_row0[slot];
+__global__ __launch_bounds__(64) void k_contract(const u32x4_t* __restrict__ dY, const int32_t* __restrict__ perm,
+                                                 const float* __restrict__ alpha_s, const int32_t* __restrict__ key_s, int b,
+                                                 int P, int mch, int m, int cg, float* __restrict__ partial) {
+    const int chunk = blockIdx.x / cg, grp = blockIdx.x % cg;
+    const int s0 = chunk * P;
+    const int s1 = min(b, s0 + P);
     const int lane = threadIdx.x;
-    const int ch = RowLoad<TR>::chunk_of(grp, lane);
+    const int ch = RowLoad<TR>::chunk_of(grp, lane, mch);
+    const int col = grp * 512 + lane * 8;
 
     float acc[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    int cur = __builtin_amdgcn_readfirstlane(key_s[s0]);
 
-    constexpr int U = 8;
-    int r = 0;
-    for (; r + U <= len; r += U) {
-        RowLoad<TR> v[U];
-        float a[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = __builtin_amdgcn_readfirstlane(perm[row0 + r + u]);
-            a[u] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[row0 + r + u])));
-            v[u].load(dY + size_t(row) * mch, ch, mch);
+    auto flush = [&](int key) {
+        if (col < m) {
+            float4* dst = reinterpret_cast<float4*>(partial + size_t(chunk + key) * m + col);
+            dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            if (col + 4 < m) dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u].fma(a[u], acc);
-    }
-    for (; r < len; ++r) {
-        const int row = __builtin_amdgcn_readfirstlane(perm[row0 + r]);
-        const float a = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[row0 + r])));
-        RowLoad<TR> v;
-        v.load(dY + size_t(row) * mch, ch, mch);
-        v.fma(a, acc);
-    }
+        for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    };
 
-    const int col = grp * 512 + lane * 8;
-    if (col < m) {
-        float4* dst = reinterpret_cast<float4*>(partial + size_t(slot) * m + col);
-        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        if (col + 4 < m) dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    // Rows are fetched in groups of U; the next group's loads are issued before the current group is consumed.
+    // Positions past the end of the chunk re-read its last row with weight 0 (no guard around the loads).
+    constexpr int U = RowLoad<TR>::kGroup;
+    auto issue = [&](RowLoad<TR> (&v)[U], float (&a)[U], int (&key)[U], int s) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int pos = min(s + u, s1 - 1);
+            const int row = __builtin_amdgcn_readfirstlane(perm[pos]);
+            const float al = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[pos])));
+            key[u] = __builtin_amdgcn_readfirstlane(key_s[pos]);
+            a[u] = (s + u < s1) ? al : 0.f;
+            v[u].load(dY + size_t(row) * mch, ch, mch);
+        }
+    };
+    auto consume = [&](const RowLoad<TR> (&v)[U], const float (&a)[U], const int (&key)[U]) {
+        if (key[0] == cur && key[U - 1] == cur) {          // the list is sorted: the whole group belongs to `cur`
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u].fma(a[u], acc);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (key[u] != cur) { flush(cur); cur = key[u]; }
+                v[u].fma(a[u], acc);
+            }
+        }
+    };
+    RowLoad<TR> va[U], vb[U];
+    float aa[U], ab[U];
+    int ka[U], kb[U];
+    issue(va, aa, ka, s0);
+    for (int s = s0; s < s1; s += 2 * U) {
+        const bool hb = s + U < s1, ha = s + 2 * U < s1;        // uniform
+        if (hb) issue(vb, ab, kb, s + U);
+        consume(va, aa, ka);
+        if (ha) issue(va, aa, ka, s + 2 * U);
+        if (hb) consume(vb, ab, kb);
     }
+    flush(cur);
 }
 
 // Btilde_j = sum of generator j's partial rows (only used by pamm_contract).
@@ -204,118 +222,82 @@ __global__ __launch_bounds__(256) void k_piece_sum(const float* __restrict__ par
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_ctb: dW (n x m) = C^T (n x k) * Btilde (k x m).  Workgroup tile 128 x 128, 4 waves of 64 x 64,
-// generators walked 32 at a time.  Both operands arrive with the generator index as the slow
-// dimension, while the MFMA wants it contiguous per lane, so each stage is transposed on its way
-// into LDS: At[l][j], Bt[c][j], rows padded by 16 bytes.
-template <typename TR> struct CtbStage;
-
-template <> struct CtbStage<Bf16> {
-    static constexpr int kRowWords = 16 + 4;       // 32 bf16 + pad
-    // A: thread -> (generator pair jp, group of 8 hidden indices lg)
-    static __device__ __forceinline__ void stage_a(const uint4* __restrict__ C, int nch, int n, int k, int j0, int l0, int tid,
-                                                   uint32_t* __restrict__ At) {
-        const int jp = tid & 15, lg = tid >> 4;
-        const int j = j0 + 2 * jp, l = l0 + 8 * lg;
-        uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
-        if (l < n) {
-            if (j < k) lo = C[size_t(j) * nch + (l >> 3)];
-            if (j + 1 < k) hi = C[size_t(j + 1) * nch + (l >> 3)];
-        }
-        const uint32_t a[4] = {lo.x, lo.y, lo.z, lo.w}, c[4] = {hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            uint32_t x = (e & 1) ? (a[e >> 1] >> 16) : (a[e >> 1] & 0xffffu);
-            uint32_t y = (e & 1) ? (c[e >> 1] & 0xffff0000u) : (c[e >> 1] << 16);
-            At[(8 * lg + e) * kRowWords + jp] = x | y;
-        }
+// k_prep: puts both operands of C^T Btilde into the layout the MFMA wants, generator index contiguous:
+//   Bt[c][j] = Btilde_j[c] = sum of generator j's pieces (rounded once to bf16 for bf16 inputs), Ct[l][j] = C_j[l],
+// rows padded with zeros to KP generators (a whole number of MFMA steps).  One thread per 16-byte chunk.
+template <typename TR> struct PackChunk;
+template <> struct PackChunk<Bf16> {
+    static __device__ __forceinline__ u32x4_t from_floats(const float (&v)[8]) {
+        return u32x4_t{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
     }
-    // B: thread -> two units of (generator pair jp, group of 4 columns cq)
-    static __device__ __forceinline__ void stage_b(const float* __restrict__ partial, const int32_t* __restrict__ sbase,
-                                                   const int32_t* __restrict__ snum, int m, int k, int j0, int c0, int tid,
-                                                   uint32_t* __restrict__ Bt) {
+    static __device__ __forceinline__ u32x4_t gather_c(const void* C, size_t n, int l, int j0, int k) {
+        const uint16_t* c = static_cast<const uint16_t*>(C);
+        uint32_t e[8];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int unit = tid + 256 * h;
-            const int jp = unit & 15, cq = unit >> 4;
-            const int c = c0 + 4 * cq;
-            float4 s[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                s[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-                const int j = j0 + 2 * jp + t;
-                if (j < k && c < m) {
-                    const int base = sbase[j], np = snum[j];
-                    for (int q = 0; q < np; ++q) {
-                        float4 v = *reinterpret_cast<const float4*>(partial + size_t(base + q) * m + c);
-                        s[t].x += v.x; s[t].y += v.y; s[t].z += v.z; s[t].w += v.w;
-                    }
-                }
-            }
-            Bt[(4 * cq + 0) * kRowWords + jp] = pack_bf16(s[0].x, s[1].x);
-            Bt[(4 * cq + 1) * kRowWords + jp] = pack_bf16(s[0].y, s[1].y);
-            Bt[(4 * cq + 2) * kRowWords + jp] = pack_bf16(s[0].z, s[1].z);
-            Bt[(4 * cq + 3) * kRowWords + jp] = pack_bf16(s[0].w, s[1].w);
-        }
+        for (int q = 0; q < 8; ++q) e[q] = (j0 + q < k) ? uint32_t(c[size_t(j0 + q) * n + l]) : 0u;
+        return u32x4_t{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
     }
 };
-
-template <> struct CtbStage<F32> {
-    static constexpr int kRowWords = 32 + 4;       // 32 fp32 + pad
-    // A: thread -> four units of (generator j, group of 4 hidden indices lq)
-    static __device__ __forceinline__ void stage_a(const uint4* __restrict__ C, int nch, int n, int k, int j0, int l0, int tid,
-                                                   uint32_t* __restrict__ At) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int unit = tid + 256 * h;
-            const int jj = unit & 31, lq = unit >> 5;
-            const int j = j0 + jj, l = l0 + 4 * lq;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (j < k && l < n) v = C[size_t(j) * nch + (l >> 2)];
-            At[(4 * lq + 0) * kRowWords + jj] = v.x;
-            At[(4 * lq + 1) * kRowWords + jj] = v.y;
-            At[(4 * lq + 2) * kRowWords + jj] = v.z;
-            At[(4 * lq + 3) * kRowWords + jj] = v.w;
-        }
+template <> struct PackChunk<F32> {
+    static __device__ __forceinline__ u32x4_t from_floats(const float (&v)[4]) {
+        return u32x4_t{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
     }
-    static __device__ __forceinline__ void stage_b(const float* __restrict__ partial, const int32_t* __restrict__ sbase,
-                                                   const int32_t* __restrict__ snum, int m, int k, int j0, int c0, int tid,
-                                                   uint32_t* __restrict__ Bt) {
+    static __device__ __forceinline__ u32x4_t gather_c(const void* C, size_t n, int l, int j0, int k) {
+        const uint32_t* c = static_cast<const uint32_t*>(C);
+        uint32_t e[4];
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int unit = tid + 256 * h;
-            const int jj = unit & 31, cq = unit >> 5;
-            const int j = j0 + jj, c = c0 + 4 * cq;
-            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j < k && c < m) {
-                const int base = sbase[j], np = snum[j];
-                for (int q = 0; q < np; ++q) {
-                    float4 v = *reinterpret_cast<const float4*>(partial + size_t(base + q) * m + c);
-                    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-                }
-            }
-            Bt[(4 * cq + 0) * kRowWords + jj] = __float_as_uint(s.x);
-            Bt[(4 * cq + 1) * kRowWords + jj] = __float_as_uint(s.y);
-            Bt[(4 * cq + 2) * kRowWords + jj] = __float_as_uint(s.z);
-            Bt[(4 * cq + 3) * kRowWords + jj] = __float_as_uint(s.w);
-        }
+        for (int q = 0; q < 4; ++q) e[q] = (j0 + q < k) ? c[size_t(j0 + q) * n + l] : 0u;
+        return u32x4_t{e[0], e[1], e[2], e[3]};
     }
 };
 
 template <typename TR>
-__global__ __launch_bounds__(256) void k_ctb(const uint4* __restrict__ C, const float* __restrict__ partial,
-                                             const int32_t* __restrict__ sbase, const int32_t* __restrict__ snum, int n, int m,
-                                             int k, int tiles_m, float* __restrict__ dW) {
-    constexpr int RW = CtbStage<TR>::kRowWords;
-    constexpr int CALLS = 32 / (2 * TR::kPerChunk);     // mma calls per 32-generator stage: 2 (bf16) or 4 (fp32)
-    __shared__ __attribute__((aligned(16))) uint32_t At[128 * RW];
-    __shared__ __attribute__((aligned(16))) uint32_t Bt[128 * RW];
+__global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const float* __restrict__ partial,
+                                              const int32_t* __restrict__ sbase, const int32_t* __restrict__ snum, int n, int m,
+                                              int k, int KC, int blocks_m, u32x4_t* __restrict__ Ct, u32x4_t* __restrict__ Bt) {
+    constexpr int JPC = TR::kPerChunk;
+    const int jg = blockIdx.y, j0 = jg * JPC;
+    if (int(blockIdx.x) < blocks_m) {
+        const int c = blockIdx.x * 256 + threadIdx.x;
+        if (c >= m) return;
+        float v[JPC];
+#pragma unroll
+        for (int q = 0; q < JPC; ++q) {
+            float s = 0.f;
+            const int j = j0 + q;
+            if (j < k) {                                   // uniform
+                const int base = sbase[j], np = snum[j];
+                for (int t = 0; t < np; ++t) s += partial[size_t(base + t) * m + c];
+            }
+            v[q] = s;
+        }
+        Bt[size_t(c) * KC + jg] = PackChunk<TR>::from_floats(v);
+    } else {
+        const int l = (blockIdx.x - blocks_m) * 256 + threadIdx.x;
+        if (l >= n) return;
+        Ct[size_t(l) * KC + jg] = PackChunk<TR>::gather_c(C, size_t(n), l, j0, k);
+    }
+}
 
+// ------------------------------------------------------------------------------------------------
+// k_ctb: dW (n x m) = C^T (n x k) * Btilde (k x m).  Workgroup tile 128 x 128, 4 waves of 64 x 64.  Both
+// operands come from k_prep with the generator index contiguous, so every MFMA fragment is one 16-byte
+// load per lane straight from L2/L1 (both operands together are a few MiB): no LDS, no barriers.  The
+// kernel is bound by writing dW.
+template <typename TR>
+__global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, const u32x4_t* __restrict__ Bt, int n, int m, int KC,
+                                             int tiles_m, float* __restrict__ dW) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wy = wave >> 1, wx = wave & 1;
-    const int l0 = (blockIdx.x / tiles_m) * 128, c0 = (blockIdx.x % tiles_m) * 128;
-    const int nch = n / TR::kPerChunk;
+    const int l0 = (blockIdx.x / tiles_m) * 128 + wy * 64, c0 = (blockIdx.x % tiles_m) * 128 + wx * 64;
 
+    const u32x4_t* arow[2];
+    const u32x4_t* brow[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        arow[q] = Ct + size_t(min(l0 + 32 * q + r, n - 1)) * KC + g;
+        brow[q] = Bt + size_t(min(c0 + 32 * q + r, m - 1)) * KC + g;
+    }
     f32x16_t acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -324,35 +306,25 @@ __global__ __launch_bounds__(256) void k_ctb(const uint4* __restrict__ C, const 
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][bq][i] = 0.f;
 
-    for (int j0 = 0; j0 < k; j0 += 32) {
-        __syncthreads();
-        CtbStage<TR>::stage_a(C, nch, n, k, j0, l0, tid, At);
-        CtbStage<TR>::stage_b(partial, sbase, snum, m, k, j0, c0, tid, Bt);
-        __syncthreads();
+#pragma unroll 4
+    for (int t = 0; t < KC; t += 2) {          // one mma call takes chunk t + g from every lane
+        u32x4_t a[2], bq[2];
 #pragma unroll
-        for (int t = 0; t < CALLS; ++t) {
-            uint4 a[2], bq[2];
+        for (int q = 0; q < 2; ++q) { a[q] = arow[q][t]; bq[q] = brow[q][t]; }
 #pragma unroll
-            for (int fa = 0; fa < 2; ++fa)
-                a[fa] = *reinterpret_cast<const uint4*>(&At[(wy * 64 + 32 * fa + r) * RW + 4 * (2 * t + g)]);
+        for (int fa = 0; fa < 2; ++fa)
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb)
-                bq[fb] = *reinterpret_cast<const uint4*>(&Bt[(wx * 64 + 32 * fb + r) * RW + 4 * (2 * t + g)]);
-#pragma unroll
-            for (int fa = 0; fa < 2; ++fa)
-#pragma unroll
-                for (int fb = 0; fb < 2; ++fb) TR::mma(a[fa], bq[fb], acc[fa][fb]);
-        }
+            for (int fb = 0; fb < 2; ++fb) TR::mma(a[fa], bq[fb], acc[fa][fb]);
     }
 
 #pragma unroll
     for (int fa = 0; fa < 2; ++fa)
 #pragma unroll
         for (int fb = 0; fb < 2; ++fb) {
-            const int c = c0 + wx * 64 + 32 * fb + r;
+            const int c = c0 + 32 * fb + r;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int l = l0 + wy * 64 + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
+                const int l = l0 + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
                 if (l < n && c < m) dW[size_t(l) * m + c] = acc[fa][fb][i];
             }
         }
@@ -363,19 +335,21 @@ __global__ __launch_bounds__(256) void k_ctb(const uint4* __restrict__ C, const 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct GradBuffers {
-    int32_t *perm, *row0, *len, *sbase, *snum;
+    int32_t *perm, *key, *sbase, *snum;
     float *alpha_s, *partial;
+    u32x4_t *ct, *bt;
 };
 
 static GradBuffers carve(const GradPlan& pl, char* ws) {
     GradBuffers g;
     g.perm = reinterpret_cast<int32_t*>(ws + pl.off_perm);
     g.alpha_s = reinterpret_cast<float*>(ws + pl.off_alpha);
-    g.row0 = reinterpret_cast<int32_t*>(ws + pl.off_row0);
-    g.len = reinterpret_cast<int32_t*>(ws + pl.off_len);
+    g.key = reinterpret_cast<int32_t*>(ws + pl.off_key);
     g.sbase = reinterpret_cast<int32_t*>(ws + pl.off_sbase);
     g.snum = reinterpret_cast<int32_t*>(ws + pl.off_snum);
     g.partial = reinterpret_cast<float*>(ws + pl.off_partial);
+    g.ct = reinterpret_cast<u32x4_t*>(ws + pl.off_ct);
+    g.bt = reinterpret_cast<u32x4_t*>(ws + pl.off_bt);
     return g;
 }
 
@@ -384,14 +358,30 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
                                   int b, int k, int m, hipStream_t s) {
     {
         ScopedSpan span(kGroup, s);
-        hipLaunchKernelGGL(k_group, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, int(pl.nslots), g.perm, g.alpha_s,
-                           g.row0, g.len, g.sbase, g.snum);
+        hipLaunchKernelGGL(k_group, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, g.perm, g.alpha_s, g.key, g.sbase,
+                           g.snum);
     }
     const int mch = m / TR::kPerChunk;
     {
         ScopedSpan span(kContract, s);
-        hipLaunchKernelGGL((k_contract<TR>), dim3((unsigned)(pl.nslots * pl.col_groups)), dim3(64), 0, s, (const uint4*)dY, g.perm,
-                           g.alpha_s, g.row0, g.len, mch, m, pl.col_groups, g.partial);
+        hipLaunchKernelGGL((k_contract<TR>), dim3((unsigned)(pl.chunks * pl.col_groups)), dim3(64), 0, s, (const u32x4_t*)dY, g.perm,
+                           g.alpha_s, g.key, b, pl.piece_rows, mch, m, pl.col_groups, g.partial);
+    }
+}
+
+template <typename TR>
+static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void* C, int n, int m, int k, float* dW, hipStream_t s) {
+    const int KC = int(pl.kpad) / TR::kPerChunk;
+    const int blocks_m = (m + 255) / 256, blocks_n = (n + 255) / 256;
+    {
+        ScopedSpan span(kPrep, s);
+        hipLaunchKernelGGL((k_prep<TR>), dim3((unsigned)(blocks_m + blocks_n), (unsigned)KC), dim3(256), 0, s, C, g.partial, g.sbase,
+                           g.snum, n, m, k, KC, blocks_m, g.ct, g.bt);
+    }
+    const int tiles_n = (n + 127) / 128, tiles_m = (m + 127) / 128;
+    {
+        ScopedSpan span(kCtb, s);
+        hipLaunchKernelGGL((k_ctb<TR>), dim3((unsigned)(tiles_n * tiles_m)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_m, dW);
     }
 }
 
@@ -402,7 +392,7 @@ using namespace pamm;
 extern "C" pamm_status pamm_contract(const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t k, int64_t m,
                                      pamm_dtype dt, float* Btilde, void* ws, size_t ws_bytes, void* stream) {
     GradPlan pl;
-    pamm_status st = plan_grad(b, per_chunk(dtype_ok(dt) ? dt : PAMM_F32), k, m, dt, &pl);   // n does not enter the layout
+    pamm_status st = plan_grad(b, per_chunk(dtype_ok(dt) ? dt : PAMM_F32), k, m, dt, &pl);   // n does not enter what is used here
     if (st != PAMM_OK) return st;
     if (k > b) return PAMM_ERR_INVALID_ARG;
     if (!f || !alpha || !dY || !Btilde) return PAMM_ERR_INVALID_ARG;
@@ -433,17 +423,12 @@ extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* a
     if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     GradBuffers g = carve(pl, (char*)ws);
-    const int tiles_n = int((n + 127) / 128), tiles_m = int((m + 127) / 128);
     if (dt == PAMM_BF16) {
         launch_group_contract<Bf16>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-        ScopedSpan span(kCtb, s);
-        hipLaunchKernelGGL((k_ctb<Bf16>), dim3((unsigned)(tiles_n * tiles_m)), dim3(256), 0, s, (const uint4*)C, g.partial, g.sbase,
-                           g.snum, int(n), int(m), int(k), tiles_m, dW);
+        launch_prep_ctb<Bf16>(pl, g, C, int(n), int(m), int(k), dW, s);
     } else {
         launch_group_contract<F32>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-        ScopedSpan span(kCtb, s);
-        hipLaunchKernelGGL((k_ctb<F32>), dim3((unsigned)(tiles_n * tiles_m)), dim3(256), 0, s, (const uint4*)C, g.partial, g.sbase,
-                           g.snum, int(n), int(m), int(k), tiles_m, dW);
+        launch_prep_ctb<F32>(pl, g, C, int(n), int(m), int(k), dW, s);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }

@@ -8,6 +8,8 @@ namespace pamm {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+// 16 bytes of a row.  A native vector (not HIP's struct-wrapped uint4) so that arrays of chunks stay in registers.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 constexpr int kWave = 64;
 
@@ -18,10 +20,10 @@ struct Bf16 {
     static constexpr int kPerChunk = 8;          // elements in 16 bytes
     // D += A(32 x K) * B(K x 32) for the K slice held in one 16-byte chunk per lane.
     // Lane (r = lane%32, g = lane/32) supplies row r of A / column r of B and the K slots 8g..8g+7.
-    static __device__ __forceinline__ void mma(const uint4& a, const uint4& b, f32x16_t& acc) {
+    static __device__ __forceinline__ void mma(const u32x4_t& a, const u32x4_t& b, f32x16_t& acc) {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
     }
-    static __device__ __forceinline__ void unpack(const uint4& v, float (&o)[8]) {
+    static __device__ __forceinline__ void unpack(const u32x4_t& v, float (&o)[8]) {
         o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
         o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
         o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
@@ -33,13 +35,13 @@ struct F32 {
     static constexpr int kElemBytes = 4;
     static constexpr int kPerChunk = 4;
     // Four 32x32x2 steps; step e takes element e of every lane's chunk, so lane group g supplies K slot g.
-    static __device__ __forceinline__ void mma(const uint4& a, const uint4& b, f32x16_t& acc) {
+    static __device__ __forceinline__ void mma(const u32x4_t& a, const u32x4_t& b, f32x16_t& acc) {
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
     }
-    static __device__ __forceinline__ void unpack(const uint4& v, float (&o)[4]) {
+    static __device__ __forceinline__ void unpack(const u32x4_t& v, float (&o)[4]) {
         o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y);
         o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
     }

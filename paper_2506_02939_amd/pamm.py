@@ -24,7 +24,7 @@ EXPORTS = [
     "pamm_compress", "pamm_compress_idx", "pamm_grad", "pamm_contract",
     "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
 ]
-NUM_KERNELS = 7
+NUM_KERNELS = 8
 
 
 class PammError(RuntimeError):
