@@ -19,33 +19,39 @@ namespace pamm {
 
 // ------------------------------------------------------------------------------------------------
 // Per-token running record of the best generators seen so far.  Equal scores are not listed twice:
-// s1 > s2 > s3 are the three largest DISTINCT score values; j1 / j2 are the lowest generator numbers
-// attaining s1 / s2; jt is the lowest generator other than j1 that attains s1 exactly (-1 if none).
-// Bit-identical generators (padding tokens sampled twice) produce bit-identical scores, so they meet
-// in jt instead of hiding the real runner-up.
+// s1 > s2 > s3 > s4 are the four largest DISTINCT score values; j1 / j2 / j3 are the lowest generator
+// numbers attaining s1 / s2 / s3; jt is the lowest generator other than j1 that attains s1 exactly
+// (-1 if none).  Bit-identical generators (padding tokens sampled twice) produce bit-identical scores,
+// so they meet in jt instead of hiding the real runners-up.
 struct Best {
-    float s1; int j1; float d1; int jt; float s2; int j2; float s3;
+    float s1; int j1; float d1; int jt; float s2; int j2; float s3; int j3; float s4;
 
-    __device__ __forceinline__ void init() { s1 = -1.f; j1 = 0; d1 = 0.f; jt = -1; s2 = -2.f; j2 = 0; s3 = -3.f; }
+    __device__ __forceinline__ void init() {
+        s1 = -1.f; j1 = 0; d1 = 0.f; jt = -1; s2 = -2.f; j2 = 0; s3 = -3.f; j3 = 0; s4 = -4.f;
+    }
 
     // generators arrive in increasing j
     __device__ __forceinline__ void push(float s, int j, float d) {
-        if (s > s1) { s3 = s2; s2 = s1; j2 = j1; s1 = s; j1 = j; d1 = d; jt = -1; }
+        if (s > s1) { s4 = s3; s3 = s2; j3 = j2; s2 = s1; j2 = j1; s1 = s; j1 = j; d1 = d; jt = -1; }
         else if (s == s1) { if (jt < 0) jt = j; }
-        else if (s > s2) { s3 = s2; s2 = s; j2 = j; }
-        else if (s < s2 && s > s3) { s3 = s; }
+        else if (s > s2) { s4 = s3; s3 = s2; j3 = j2; s2 = s; j2 = j; }
+        else if (s == s2) { }
+        else if (s > s3) { s4 = s3; s3 = s; j3 = j; }
+        else if (s < s3 && s > s4) { s4 = s; }
     }
 
     __device__ __forceinline__ void insert_lower(float s, int j) {   // s < s1
-        if (s > s2) { s3 = s2; s2 = s; j2 = j; }
+        if (s > s2) { s4 = s3; s3 = s2; j3 = j2; s2 = s; j2 = j; }
         else if (s == s2) { j2 = min(j2, j); }
-        else if (s > s3) { s3 = s; }
+        else if (s > s3) { s4 = s3; s3 = s; j3 = j; }
+        else if (s == s3) { j3 = min(j3, j); }
+        else if (s > s4) { s4 = s; }
     }
 
     // union with a record built over a disjoint set of generators
     __device__ __forceinline__ void merge(const Best& o) {
         if (o.s1 > s1) {
-            s3 = s2; s2 = s1; j2 = j1;
+            s4 = s3; s3 = s2; j3 = j2; s2 = s1; j2 = j1;
             s1 = o.s1; j1 = o.j1; d1 = o.d1; jt = o.jt;
         } else if (o.s1 == s1) {
             int lo = min(j1, o.j1), t = max(j1, o.j1);
@@ -57,7 +63,21 @@ struct Best {
             insert_lower(o.s1, o.j1);
         }
         insert_lower(o.s2, o.j2);
-        if (o.s3 < s2 && o.s3 > s3) s3 = o.s3;
+        insert_lower(o.s3, o.j3);
+        if (o.s4 < s3 && o.s4 > s4) s4 = o.s4;      // three larger values of o are already in: at best fourth
+    }
+
+    // 32-byte record: generator numbers fit 16 bits (k <= 16384); 0xffff stands for "none"
+    __device__ __forceinline__ void store(u32x4_t* dst) const {
+        dst[0] = u32x4_t{__float_as_uint(s1), __float_as_uint(d1), __float_as_uint(s2), __float_as_uint(s3)};
+        dst[1] = u32x4_t{__float_as_uint(s4), uint32_t(j1) | (uint32_t(jt) << 16), uint32_t(j2) | (uint32_t(j3) << 16), 0u};
+    }
+    __device__ __forceinline__ void load(const u32x4_t* src) {
+        const u32x4_t p = src[0], q = src[1];
+        s1 = __uint_as_float(p.x); d1 = __uint_as_float(p.y); s2 = __uint_as_float(p.z); s3 = __uint_as_float(p.w);
+        s4 = __uint_as_float(q.x);
+        j1 = int(q.y & 0xffffu); jt = int(q.y >> 16); jt = jt == 0xffff ? -1 : jt;
+        j2 = int(q.z & 0xffffu); j3 = int(q.z >> 16);
     }
 };
 
@@ -105,51 +125,73 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_score.  Workgroup = 4 waves; wave w owns 32*TT tokens; the workgroup owns one column block of
+// k_score.  Workgroup = NW waves; wave w owns 32*TT tokens; the workgroup owns one column block of
 // 32*TG generators.  Roles in the 32x32 MFMA: A operand = generators, B operand = tokens, so a lane
-// ends up holding scores of ONE token (lane%32) against 16*TG generators per token fragment and the
-// argmax runs in registers; only the two half-waves have to be merged at the end.
+// ends up holding scores of ONE token (lane%32) against 16*TG generators per token fragment.
 //
-// The hidden dimension is walked in "super-steps" of 8 chunks (128 bytes of a row): lane (r,g) loads
-// the 64 contiguous bytes [64g, 64g+64) of that window from its row, i.e. 4 chunks that feed 4
-// MFMA K-steps.  Which hidden index lands in which K slot is irrelevant for a dot product as long
-// as the generator operand uses the same map, which it does (same (g,u) -> chunk rule).
+// The hidden dimension is walked in "super-steps" of 8 chunks (128 bytes of a row); an MFMA step u takes
+// chunk 4g+u of the window from lane group g, for the token operand and the generator operand alike (the
+// order of the hidden index inside a dot product is free, as long as both operands agree).
 //
-// C is staged through LDS in stages of 64/TG chunks per generator (32 KiB per stage), double
-// buffered: global loads of stage s+1 are in flight while stage s is consumed.
-template <typename TR, int TG, int TT, bool ALIGNED>
-__global__ __launch_bounds__(256) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                               const float* __restrict__ inv, int b, int nch, int k, int ncb,
-                                               u32x4_t* __restrict__ cand) {
+// X: each wave streams its own tokens with fully coalesced loads (8 lanes cover the 128 bytes of one row and
+// super-step), D-1 super-steps ahead in registers, then passes them through a wave-private LDS tile to reach
+// the MFMA layout (lane r needs 16 bytes of row r).  Inside the tile, row r keeps chunk c at position c^(r&7),
+// which makes both the lane-linear writes and the column reads free of bank conflicts.
+// C: staged through LDS in stages of 64/TG chunks per generator (32 KiB per stage), double buffered; the
+// global loads of stage s+1 are in flight while stage s is consumed.
+// LDS fragments for MFMA step u+1 are requested before the MFMAs of step u are issued.
+#if defined(PAMM_DBG_TIME)
+__device__ unsigned long long g_dbg_time[4 * 4096];
+#define PAMM_STAMP(slot) do { if (lane == 0 && wave == 0 && blockIdx.x < 4096) g_dbg_time[blockIdx.x * 4 + (slot)] = wall_clock64(); } while (0)
+#else
+#define PAMM_STAMP(slot) do { } while (0)
+#endif
+
+template <typename TR, int TG, int TT, int NW, bool ALIGNED>
+__global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
+                                                   const float* __restrict__ inv, int b, int nch, int k, int ncb,
+                                                   u32x4_t* __restrict__ cand) {
+    constexpr int NT = 64 * NW;
     constexpr int GB = 32 * TG;          // generators per column block
     constexpr int SS = 8 / TG;           // super-steps per stage
     constexpr int CPS = 8 * SS;          // chunks per generator per stage
     constexpr int RS = CPS + 1;          // LDS row stride in chunks (odd: conflict-free 16-byte reads down a column)
-    constexpr int LOADS = GB * CPS / 256;   // = 8 chunks per thread per stage
+    constexpr int CLOADS = GB * CPS / NT;   // chunks of C per thread per stage
+    constexpr int CBUF = GB * RS;        // chunks per C buffer
+    constexpr int XSLOT = TT * 256;      // chunks per X slot (TT fragments of 32 rows x 8 chunks)
+    constexpr int D = 4;                 // X ring depth in registers (super-steps)
+    constexpr int UN = SS > D ? SS : D;  // super-steps per unrolled body: a multiple of SS and of D
+    static_assert(GB * CPS % NT == 0, "stage does not divide over the threads");
 
-    __shared__ u32x4_t lds_c[2][GB * RS];
-    __shared__ float lds_inv[GB];
-
+    __shared__ u32x4_t lds_raw[2 * CBUF + NW * 2 * XSLOT];
+    __shared__ __attribute__((aligned(16))) float lds_inv[GB];
+    u32x4_t* const lds_c = lds_raw;                                         // [2][CBUF]
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
+    u32x4_t* const lds_x = lds_raw + 2 * CBUF + wave * (2 * XSLOT);         // [2][XSLOT], private to this wave
     const int cb = blockIdx.x % ncb;
     const int rt = blockIdx.x / ncb;
     const int gen0 = cb * GB;
 
-    if (tid < GB) {
-        int j = gen0 + tid;
-        lds_inv[tid] = j < k ? inv[j] : -1.f;      // negative marks a slot past the last generator
+    PAMM_STAMP(0);
+    for (int t = tid; t < GB; t += NT) {
+        const int j = gen0 + t;
+        lds_inv[t] = j < k ? inv[j] : -1.f;        // negative marks a slot past the last generator
     }
 
-    // token rows of this lane (clamped: rows past the end are computed on a valid row and never stored)
-    const int row_base = rt * (128 * TT) + wave * (32 * TT);
-    const u32x4_t* xrow[TT];
+    // coalesced view of this wave's tokens: load i of fragment tt covers rows 8i .. 8i+7, lane L the row 8i + L/8
+    // and the chunk (L%8) ^ (L/8) of the window, so that it lands at position L%8 of its row in the tile
+    const int row_base = rt * (32 * TT * NW) + wave * (32 * TT);
+    const int xchunk = (lane & 7) ^ (lane >> 3);
+    const u32x4_t* xrow[TT][4];
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        int row = row_base + 32 * tt + r;
-        row = row < b ? row : b - 1;
-        xrow[tt] = X + size_t(row) * nch;
-    }
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int row = row_base + 32 * tt + 8 * i + (lane >> 3);
+            row = row < b ? row : b - 1;           // rows past the end are computed on a valid row and never stored
+            xrow[tt][i] = X + size_t(row) * nch;
+        }
 
     f32x16_t acc[TG][TT];
 #pragma unroll
@@ -162,56 +204,64 @@ __global__ __launch_bounds__(256) void k_score(const u32x4_t* __restrict__ X, co
     const int nstages = (nch + CPS - 1) / CPS;
     const int nss = (nch + 7) / 8;               // super-steps
 
-    u32x4_t creg[LOADS];
+    u32x4_t creg[CLOADS];
     auto load_c = [&](int stage) {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            int q = tid + 256 * i;
-            int row = q / CPS, cc = q % CPS;
+        for (int i = 0; i < CLOADS; ++i) {
+            const int q = tid + NT * i;
+            const int row = q / CPS, cc = q % CPS;
             const int j = gen0 + row, c = stage * CPS + cc;
             // Clamped addresses, no guard and no mask: a guarded load costs a branch per chunk, and a mask makes
             // the compiler wait for the load where it is issued.  Rows past the last generator are ignored by
             // the epilogue; chunks past the end of a row meet zero chunks of X.
+#if defined(PAMM_DBG_NOC)
+            creg[i] = u32x4_t{uint32_t(j), uint32_t(c), 2u, 3u};
+#else
             creg[i] = C[size_t(min(j, k - 1)) * nch + min(c, nch - 1)];
+#endif
         }
     };
     auto store_c = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            int q = tid + 256 * i;
-            lds_c[buf][(q / CPS) * RS + (q % CPS)] = creg[i];
+        for (int i = 0; i < CLOADS; ++i) {
+            const int q = tid + NT * i;
+            lds_c[buf * CBUF + (q / CPS) * RS + (q % CPS)] = creg[i];
         }
     };
-    // X ring: D super-steps of this lane's chunks live in registers; loads run D-1 super-steps ahead of the
-    // MFMAs so that every wave keeps (D-1) * TT * 4 KiB of X in flight.
-    constexpr int D = (TG * TT >= 16) ? 2 : 4;
-    constexpr int UN = SS > D ? SS : D;          // super-steps per unrolled body: a multiple of SS and of D
     u32x4_t xr[D][TT][4];
     auto load_x = [&](u32x4_t (&dst)[TT][4], int sstep) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int i = 0; i < 4; ++i) {
                 if (ALIGNED) {        // rows are whole super-steps: clamp the super-step, nothing to mask
 #if defined(PAMM_DBG_NOX)
-                    dst[tt][u] = u32x4_t{uint32_t(sstep), 1u, 2u, 3u};
+                    dst[tt][i] = u32x4_t{uint32_t(sstep), 1u, 2u, 3u};
 #else
-                    dst[tt][u] = xrow[tt][min(sstep, nss - 1) * 8 + 4 * g + u];
+                    dst[tt][i] = xrow[tt][i][min(sstep, nss - 1) * 8 + xchunk];
 #endif
                 } else {
-                    const int c = sstep * 8 + 4 * g + u;
+                    const int c = sstep * 8 + xchunk;
                     const uint32_t keep = c < nch ? 0xffffffffu : 0u;
-                    dst[tt][u] = xrow[tt][min(c, nch - 1)] & keep;
+                    dst[tt][i] = xrow[tt][i][min(c, nch - 1)] & keep;
                 }
             }
+    };
+    auto stash_x = [&](const u32x4_t (&src)[TT][4], int slot) {      // registers -> this wave's LDS tile
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) lds_x[slot * XSLOT + tt * 256 + i * 64 + lane] = src[tt][i];
     };
 
     load_c(0);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
     store_c(0);
+    stash_x(xr[0], 0);
     __syncthreads();
 
+    PAMM_STAMP(1);
     const int nbody = (nss + UN - 1) / UN;
     int buf = 0, stage = 0;
     for (int bi = 0; bi < nbody; ++bi) {
@@ -223,61 +273,161 @@ __global__ __launch_bounds__(256) void k_score(const u32x4_t* __restrict__ X, co
                 if (stage + 1 < nstages) load_c(stage + 1);
             }
             load_x(xr[(p + D - 1) % D], gs + D - 1);
+#if defined(PAMM_DBG_NOSTASH)
+            acc[0][0][1] += __uint_as_float(xr[(p + 1) % D][0][0].x ^ xr[(p + 1) % D][0][1].y ^ xr[(p + 1) % D][0][2].z ^ xr[(p + 1) % D][0][3].w);
+#else
+            stash_x(xr[(p + 1) % D], (gs + 1) & 1);          // next super-step's tokens into the other slot
+#endif
+#if defined(PAMM_DBG_NOCOMP)
+            if (gs < nss) {
+                const u32x4_t* cbuf = lds_c + buf * CBUF;
+                const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
+                acc[0][0][0] += __uint_as_float(cbuf[tid].x ^ xbuf[lane].y);
+            }
+#else
             if (gs < nss) {                                  // uniform; only false in the tail of the last body
-                const u32x4_t* cbuf = lds_c[buf];
+                const u32x4_t* cbuf = lds_c + buf * CBUF;
+                const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
+                u32x4_t a[2][TG], bx[2][TT];
+                auto fetch = [&](int u, int which) {
+#pragma unroll
+                    for (int tg = 0; tg < TG; ++tg) a[which][tg] = cbuf[(32 * tg + r) * RS + (p % SS) * 8 + 4 * g + u];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) bx[which][tt] = xbuf[tt * 256 + r * 8 + ((4 * g + u) ^ (r & 7))];
+                };
+                fetch(0, 0);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    u32x4_t a[TG];
-#pragma unroll
-                    for (int tg = 0; tg < TG; ++tg) a[tg] = cbuf[(32 * tg + r) * RS + (p % SS) * 8 + 4 * g + u];
+                    if (u < 3) fetch(u + 1, (u + 1) & 1);
 #pragma unroll
                     for (int tg = 0; tg < TG; ++tg)
 #pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) {
-#if defined(PAMM_DBG_NOMMA)
-                            acc[tg][tt][0] += __uint_as_float(a[tg].x ^ xr[p % D][tt][u].x);
-#else
-                            TR::mma(a[tg], xr[p % D][tt][u], acc[tg][tt]);
-#endif
-                        }
+                        for (int tt = 0; tt < TT; ++tt) TR::mma(a[u & 1][tg], bx[u & 1][tt], acc[tg][tt]);
                 }
             }
+#endif
             if (p % SS == SS - 1) {                          // the stage ends: publish the next one
                 if (stage + 1 < nstages) store_c(buf ^ 1);
+#if defined(PAMM_DBG_NOBAR)
+                wave_lds_sync();
+#else
                 __syncthreads();
+#endif
                 buf ^= 1;
+            } else {
+                wave_lds_sync();                             // the stashed tokens are read by other lanes of this wave
             }
         }
     }
 
-    // epilogue: D layout of the 32x32 MFMA: register i of lane (r,g) is generator 8*(i/4)+4*g+(i%4), token r
+    // Epilogue.  D layout of the 32x32 MFMA: register i of lane (r,g) is generator 8*(i/4)+4*g+(i%4), token r.
+    // The scores go through LDS (all tiles are free after the last barrier) so that the scan over generators
+    // is a small rolled loop instead of hundreds of unrolled compare/select chains: each pass dumps PG
+    // generators x 32 tokens per wave, then lane (r,g) scans half of them for token r in increasing order.
+    PAMM_STAMP(2);
+    constexpr int PFMAX = NW == 8 ? 2 : 4;
+    constexpr int PF = TG < PFMAX ? TG : PFMAX;   // fragments per pass
+    constexpr int PG = 32 * PF;              // generators per pass
+    constexpr int SROW = PG + 4;             // floats per token row (padding: conflict-free 16-byte accesses)
+    static_assert(NW * 32 * SROW * sizeof(float) <= sizeof(lds_raw), "score dump does not fit");
+    float* sdump = reinterpret_cast<float*>(lds_raw) + wave * (32 * SROW);
+    const float kClose = 1.f - 0x1p-12f;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        Best best;
-        best.init();
+        auto dump = [&](int h) {                 // scores of pass h -> this wave's LDS tile, [token][generator]
 #pragma unroll
-        for (int tg = 0; tg < TG; ++tg) {
+            for (int pf = 0; pf < PF; ++pf)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                int jl = 32 * tg + 8 * (i >> 2) + 4 * g + (i & 3);
-                float iv = lds_inv[jl];
-                float d = acc[tg][tt][i];
-                float s = d * d * iv;
-                if (iv >= 0.f) best.push(s, gen0 + jl, d);
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16_t& v = acc[h * PF + pf][tt];
+                    *reinterpret_cast<float4*>(&sdump[r * SROW + 32 * pf + 8 * q + 4 * g]) =
+                        make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+                }
+            wave_lds_sync();
+        };
+        const float* srow = &sdump[r * SROW + g * (PG / 2)];
+
+        // Round 1 (always): per lane, over its half of every pass: the largest score m1 (lowest j on ties), the
+        // lowest other generator reaching it exactly (jt), and the largest score strictly below it (m2).
+        float m1 = -1.f, m2 = -2.f, dm = 0.f;
+        int jm = 0, jt = -1;
+#pragma unroll
+        for (int h = 0; h < TG / PF; ++h) {
+            dump(h);
+            const int jl0 = h * PG + g * (PG / 2);
+#pragma unroll 2
+            for (int c = 0; c < PG / 2; c += 4) {
+                const float4 d4 = *reinterpret_cast<const float4*>(&srow[c]);
+                const float4 iv4 = *reinterpret_cast<const float4*>(&lds_inv[jl0 + c]);
+                const float dd[4] = {d4.x, d4.y, d4.z, d4.w}, iv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float sc = iv[e] >= 0.f ? dd[e] * dd[e] * iv[e] : -3.f;      // slots past the last generator
+                    const int j = gen0 + jl0 + c + e;
+                    const bool up = sc > m1, tie = sc == m1;
+                    m2 = up ? m1 : ((!tie && sc > m2) ? sc : m2);
+                    jt = up ? -1 : ((tie && jt < 0) ? j : jt);
+                    dm = up ? dd[e] : dm;
+                    jm = up ? j : jm;
+                    m1 = up ? sc : m1;
+                }
+            }
+            wave_lds_sync();
+        }
+        // the two lanes of a token join their halves
+        {
+            const float o1 = __shfl_xor(m1, 32), o2 = __shfl_xor(m2, 32), od = __shfl_xor(dm, 32);
+            const int oj = __shfl_xor(jm, 32), ot = __shfl_xor(jt, 32);
+            if (o1 > m1) {
+                m2 = fmaxf(fmaxf(m1, m2), o2);
+                m1 = o1; jm = oj; dm = od; jt = ot;
+            } else if (o1 == m1) {
+                int t = max(jm, oj);
+                if (jt >= 0) t = min(t, jt);
+                if (ot >= 0) t = min(t, ot);
+                if (oj < jm) dm = od;
+                jm = min(jm, oj); jt = t;
+                m2 = fmaxf(m2, o2);
+            } else {
+                m2 = fmaxf(fmaxf(o1, o2), m2);
             }
         }
-        Best o;
-        o.s1 = __shfl_xor(best.s1, 32); o.j1 = __shfl_xor(best.j1, 32); o.d1 = __shfl_xor(best.d1, 32);
-        o.jt = __shfl_xor(best.jt, 32); o.s2 = __shfl_xor(best.s2, 32); o.j2 = __shfl_xor(best.j2, 32);
-        o.s3 = __shfl_xor(best.s3, 32);
-        best.merge(o);
-        int row = row_base + 32 * tt + r;
-        if (g == 0 && row < b) {
-            u32x4_t* dst = cand + (size_t(row) * ncb + cb) * 2;
-            dst[0] = u32x4_t{__float_as_uint(best.s1), uint32_t(best.j1), __float_as_uint(best.d1), uint32_t(best.jt)};
-            dst[1] = u32x4_t{__float_as_uint(best.s2), uint32_t(best.j2), __float_as_uint(best.s3), 0u};
+        const bool close = m1 > 0.f && m2 >= m1 * kClose;
+        const int row = row_base + 32 * tt + r;
+        if (__builtin_amdgcn_ballot_w64(close) == 0ull) {
+            // nobody in this wave has a distinct runner-up within 2^-12: the record is the winner (and its exact ties)
+            Best best;
+            best.init();
+            best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
+            if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
+        } else {
+            // Round 2 (rare): the complete four-value record for the whole wave
+            Best best;
+            best.init();
+#pragma unroll
+            for (int h = 0; h < TG / PF; ++h) {
+                dump(h);
+                const int jl0 = h * PG + g * (PG / 2);
+#pragma unroll 1
+                for (int c = 0; c < PG / 2; c += 4) {
+                    const float4 d4 = *reinterpret_cast<const float4*>(&srow[c]);
+                    const float4 iv4 = *reinterpret_cast<const float4*>(&lds_inv[jl0 + c]);
+                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w}, iv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (iv[e] >= 0.f) best.push(dd[e] * dd[e] * iv[e], gen0 + jl0 + c + e, dd[e]);
+                }
+                wave_lds_sync();
+            }
+            Best o;
+            o.s1 = __shfl_xor(best.s1, 32); o.j1 = __shfl_xor(best.j1, 32); o.d1 = __shfl_xor(best.d1, 32);
+            o.jt = __shfl_xor(best.jt, 32); o.s2 = __shfl_xor(best.s2, 32); o.j2 = __shfl_xor(best.j2, 32);
+            o.s3 = __shfl_xor(best.s3, 32); o.j3 = __shfl_xor(best.j3, 32); o.s4 = __shfl_xor(best.s4, 32);
+            best.merge(o);
+            if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
         }
     }
+    PAMM_STAMP(3);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -285,6 +435,7 @@ __global__ __launch_bounds__(256) void k_score(const u32x4_t* __restrict__ X, co
 template <typename TR>
 __device__ __forceinline__ double wave_dot(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ c, int nch, int lane) {
     double acc = 0.0;
+#pragma unroll 4
     for (int q = lane; q < nch; q += kWave) {
         float a[TR::kPerChunk], bq[TR::kPerChunk];
         TR::unpack(x[q], a);
@@ -308,47 +459,46 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
     st.init();
     if (valid) {
         for (int cb = 0; cb < ncb; ++cb) {
-            const u32x4_t* src = cand + (size_t(row) * ncb + cb) * 2;
-            u32x4_t p = src[0], q = src[1];
             Best o;
-            o.s1 = __uint_as_float(p.x); o.j1 = int(p.y); o.d1 = __uint_as_float(p.z); o.jt = int(p.w);
-            o.s2 = __uint_as_float(q.x); o.j2 = int(q.y); o.s3 = __uint_as_float(q.z);
+            o.load(cand + (size_t(row) * ncb + cb) * 2);
             if (cb == 0) st = o; else st.merge(o);
         }
     }
     int fi = st.j1;
     float al = st.d1 * inv[st.j1];
-    // 0: fp32 decision stands; 1: re-decide between two generators in fp64; 2: re-decide among all generators
-    int mode = 0, other = st.j2;
+    // Rows whose leading scores are within 2^-12 (relative) of each other are re-decided in fp64: among up to four
+    // named candidates when at most three distinct values are that close, among all generators otherwise.
+    int ncand = 0, c1 = 0, c2 = 0, c3 = 0;     // extra candidates beside j1 (ncand = 4 means "all generators")
     if (valid && st.s1 > 0.f) {
         const float thr = st.s1 * (1.f - 0x1p-12f);
-        bool tie_other = false;
-        if (st.jt >= 0)
-            tie_other = !(hash[st.j1] == hash[st.jt] && __double_as_longlong(cn2[st.j1]) == __double_as_longlong(cn2[st.jt]));
-        const bool close2 = st.s2 >= thr, close3 = st.s3 >= thr;
-        if (tie_other || close2) {
-            mode = (close3 || (tie_other && close2)) ? 2 : 1;
-            other = tie_other ? st.jt : st.j2;
-        }
+        if (st.jt >= 0 &&
+            !(hash[st.j1] == hash[st.jt] && __double_as_longlong(cn2[st.j1]) == __double_as_longlong(cn2[st.jt])))
+            c1 = st.jt, ncand = 1;
+        if (st.s2 >= thr) { (ncand == 0 ? c1 : c2) = st.j2; ++ncand; }
+        if (st.s3 >= thr) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
+        if (st.s4 >= thr) ncand = 4;
     }
-    unsigned long long pending = __ballot(mode != 0);
+    unsigned long long pending = __ballot(ncand != 0);
     while (pending) {
         const int L = __ffsll((long long)pending) - 1;
         pending &= pending - 1;
-        const int rrow = __shfl(row, L), rmode = __shfl(mode, L);
-        const int ja = __shfl(st.j1, L), jb = __shfl(other, L);
+        const int rrow = __shfl(row, L), rn = __shfl(ncand, L);
+        int cj[4] = {__shfl(st.j1, L), __shfl(c1, L), __shfl(c2, L), __shfl(c3, L)};
         const u32x4_t* xr = X + size_t(rrow) * nch;
         double bs = -1.0, bd = 0.0, bc = 1.0;
         int bj = 0;
         auto eval = [&](int j) {
             double d = wave_dot<TR>(xr, C + size_t(j) * nch, nch, lane);
-            double c2 = cn2[j];
-            double s = c2 > 0.0 ? d * d / c2 : 0.0;
-            if (s > bs) { bs = s; bd = d; bc = c2; bj = j; }       // strict: lowest j keeps a tie
+            double c2n = cn2[j];
+            double s = c2n > 0.0 ? d * d / c2n : 0.0;
+            if (s > bs) { bs = s; bd = d; bc = c2n; bj = j; }       // strict: lowest j keeps a tie
         };
-        if (rmode == 1) {
-            eval(min(ja, jb));
-            eval(max(ja, jb));
+        if (rn < 4) {
+            const int cnt = rn + 1;
+            // candidates in increasing j (all values are wave-uniform)
+            for (int a = 1; a < cnt; ++a)
+                for (int q = a; q > 0 && cj[q] < cj[q - 1]; --q) { int t = cj[q]; cj[q] = cj[q - 1]; cj[q - 1] = t; }
+            for (int a = 0; a < cnt; ++a) eval(cj[a]);
         } else {
             for (int j = 0; j < k; ++j) eval(j);
         }
@@ -367,26 +517,35 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <typename TR, int TG>
-static void launch_score_tt(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
-                            u32x4_t* cand, hipStream_t s) {
+template <typename TR, int TG, int TT, int NW>
+static void launch_score_cfg(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
+                             u32x4_t* cand, hipStream_t s) {
     dim3 grid((unsigned)(pl.row_tiles * pl.ncb));
-    const bool aligned = nch % 8 == 0;      // every row is a whole number of 128-byte super-steps
-#define PAMM_LAUNCH_SCORE(TTV, AL) \
-    hipLaunchKernelGGL((k_score<TR, TG, TTV, AL>), grid, dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv, b, nch, k, pl.ncb, cand)
-    if (pl.tt == 2) { if (aligned) PAMM_LAUNCH_SCORE(2, true); else PAMM_LAUNCH_SCORE(2, false); }
-    else            { if (aligned) PAMM_LAUNCH_SCORE(1, true); else PAMM_LAUNCH_SCORE(1, false); }
-#undef PAMM_LAUNCH_SCORE
+    if (nch % 8 == 0)      // every row is a whole number of 128-byte super-steps
+        hipLaunchKernelGGL((k_score<TR, TG, TT, NW, true>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv,
+                           b, nch, k, pl.ncb, cand);
+    else
+        hipLaunchKernelGGL((k_score<TR, TG, TT, NW, false>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv,
+                           b, nch, k, pl.ncb, cand);
+}
+
+template <typename TR, int TG>
+static void launch_score_tg(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
+                            u32x4_t* cand, hipStream_t s) {
+    if (pl.tt == 2) launch_score_cfg<TR, TG, 2, 4>(pl, X, C, inv, b, nch, k, cand, s);
+    else if (pl.nw == 8) launch_score_cfg<TR, TG, 1, 8>(pl, X, C, inv, b, nch, k, cand, s);
+    else if (pl.nw == 4) launch_score_cfg<TR, TG, 1, 4>(pl, X, C, inv, b, nch, k, cand, s);
+    else launch_score_cfg<TR, TG, 1, 2>(pl, X, C, inv, b, nch, k, cand, s);
 }
 
 template <typename TR>
 static void launch_score(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
                          u32x4_t* cand, hipStream_t s) {
     switch (pl.tg) {
-        case 1: launch_score_tt<TR, 1>(pl, X, C, inv, b, nch, k, cand, s); break;
-        case 2: launch_score_tt<TR, 2>(pl, X, C, inv, b, nch, k, cand, s); break;
-        case 4: launch_score_tt<TR, 4>(pl, X, C, inv, b, nch, k, cand, s); break;
-        default: launch_score_tt<TR, 8>(pl, X, C, inv, b, nch, k, cand, s); break;
+        case 1: launch_score_tg<TR, 1>(pl, X, C, inv, b, nch, k, cand, s); break;
+        case 2: launch_score_tg<TR, 2>(pl, X, C, inv, b, nch, k, cand, s); break;
+        case 4: launch_score_tg<TR, 4>(pl, X, C, inv, b, nch, k, cand, s); break;
+        default: launch_score_tg<TR, 8>(pl, X, C, inv, b, nch, k, cand, s); break;
     }
 }
 
@@ -495,3 +654,9 @@ extern "C" pamm_status pamm_compress(const void* X, int64_t b, int64_t n, int64_
     ring.used[slot] = true;
     return st;
 }
+
+#if defined(PAMM_DBG_TIME)
+extern "C" int pamm_dbg_read_time(unsigned long long* out_host, int count) {
+    return int(hipMemcpyFromSymbol(out_host, HIP_SYMBOL(pamm::g_dbg_time), sizeof(unsigned long long) * count));
+}
+#endif

@@ -41,10 +41,17 @@ __device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, int i0,
     }
 }
 
-__global__ __launch_bounds__(1024) void k_group(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                int P, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
-                                                int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
-                                                int32_t* __restrict__ snum) {
+// Entries b .. roundup(b,16)-1 of the sorted lists: a valid row, weight 0, the key of the last real entry.
+__device__ __forceinline__ void pad_lists(int32_t* __restrict__ perm, float* __restrict__ alpha_s, int32_t* __restrict__ key_s,
+                                          int b, int last_key) {
+    for (int q = b; q < (b + 15) / 16 * 16; ++q) { perm[q] = 0; alpha_s[q] = 0.f; key_s[q] = last_key; }
+}
+
+// Generic version: two passes over f from L2, any b.
+__global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
+                                                       int P, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
+                                                       int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
+                                                       int32_t* __restrict__ snum) {
     const int j = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const long long per_wave = (((long long)b + 15) / 16 + 255) / 256 * 256;
@@ -104,6 +111,186 @@ __global__ __launch_bounds__(1024) void k_group(const int32_t* __restrict__ f, c
     if (tid == 0) {
         sbase[j] = seg_start / P + j;
         snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
+        if (count > 0 && seg_start + count == b) pad_lists(perm, alpha_s, key_s, b, j);
+    }
+}
+
+// Version for b <= 16 waves * NV * 256 rows (NV <= 16, i.e. b <= 65536): every lane keeps its 4*NV keys in
+// registers, so f is read once and both passes run out of registers.
+template <int NV>
+__global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
+                                                     int P, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
+                                                     int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
+                                                     int32_t* __restrict__ snum) {
+    const int j = blockIdx.x;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r0 = wave * (NV * 256);
+    int key[NV][4];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) load_keys(f, r0 + v * 256 + 4 * lane, b, k, key[v]);
+
+    int lt = 0, eq = 0;
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { lt += key[v][c] < j; eq += key[v][c] == j; }
+    lt = wave_sum(lt);
+    eq = wave_sum(eq);
+    __shared__ int s_lt[16], s_eq[16];
+    if (lane == 0) { s_lt[wave] = lt; s_eq[wave] = eq; }
+    __syncthreads();
+    int seg_start = 0, count = 0, woff = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        seg_start += s_lt[w];
+        woff += (w < wave) ? s_eq[w] : 0;
+        count += s_eq[w];
+    }
+
+    if (eq > 0) {                          // wave-uniform
+        int pos = seg_start + woff;
+        const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int i0 = r0 + v * 256 + 4 * lane;
+            int before = 0, total = 0;
+            bool hit[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                hit[c] = key[v][c] == j;
+                unsigned long long m = __ballot(hit[c]);
+                before += __popcll(m & below);
+                total += __popcll(m);
+            }
+            if (total > 0) {               // wave-uniform
+                int within = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (hit[c]) {
+                        perm[pos + before + within] = i0 + c;
+                        alpha_s[pos + before + within] = alpha[i0 + c];
+                        key_s[pos + before + within] = j;
+                        ++within;
+                    }
+                }
+                pos += total;
+            }
+        }
+    }
+    if (tid == 0) {
+        sbase[j] = seg_start / P + j;
+        snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
+        if (count > 0 && seg_start + count == b) pad_lists(perm, alpha_s, key_s, b, j);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Grouping in O(b) for k <= 2048: a counting sort over slices of 4096 rows.
+//   k_hist     one workgroup per slice: histogram of the slice's keys (LDS atomics), written to table[slice][j]
+//   k_scatter  one workgroup per slice: start of every generator's list (sum over all slices, scanned over j), plus
+//              the rows of earlier slices, plus the rows of earlier waves of this slice; then every row takes the
+//              next free position of its (wave, generator) counter.
+// Inside a wave the order of equal keys is the order in which the LDS unit serves the lanes of one atomic
+// instruction; it does not depend on timing, so the list, and every sum formed from it, is the same on every call.
+constexpr int kSliceRows = 4096;
+constexpr int kScatterMaxK = 2048;
+
+__global__ __launch_bounds__(1024) void k_hist(const int32_t* __restrict__ f, int b, int k, int32_t* __restrict__ table) {
+    extern __shared__ int hist[];
+    const int tid = threadIdx.x;
+    for (int j = tid; j < k; j += 1024) hist[j] = 0;
+    __syncthreads();
+    int key[4];
+    const int i0 = blockIdx.x * kSliceRows + 4 * tid;
+    load_keys(f, i0, b, k, key);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        if (key[c] < k) atomicAdd(&hist[key[c]], 1);
+    __syncthreads();
+    for (int j = tid; j < k; j += 1024) table[size_t(blockIdx.x) * k + j] = hist[j];
+}
+
+__global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
+                                                  int P, int nslices, const int32_t* __restrict__ table,
+                                                  int32_t* __restrict__ perm, float* __restrict__ alpha_s,
+                                                  int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
+                                                  int32_t* __restrict__ snum) {
+    extern __shared__ int lds[];
+    int* wh = lds;                 // [16][k]  per-wave counts, later per-wave next free position inside the generator's list
+    int* tot = lds + 16 * k;       // [k]      rows per generator (whole batch), later start of the generator's list
+    __shared__ int wsum[16];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int slice = blockIdx.x;
+
+    for (int q = tid; q < 16 * k; q += 1024) wh[q] = 0;
+    __syncthreads();
+    int key[4];
+    const int i0 = slice * kSliceRows + 4 * tid;      // wave w owns rows [256 w, 256 w + 256) of the slice
+    load_keys(f, i0, b, k, key);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        if (key[c] < k) atomicAdd(&wh[wave * k + key[c]], 1);
+    __syncthreads();
+
+    for (int j = tid; j < k; j += 1024) {
+        int before = 0, total = 0;
+        for (int s = 0; s < nslices; ++s) {
+            const int c = table[size_t(s) * k + j];
+            before += s < slice ? c : 0;
+            total += c;
+        }
+        int run = before;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int c = wh[w * k + j];
+            wh[w * k + j] = run;
+            run += c;
+        }
+        tot[j] = total;
+    }
+    __syncthreads();
+
+    // exclusive scan of tot[] over the generators, 1024 at a time
+    int carry = 0;
+    for (int base = 0; base < k; base += 1024) {
+        const int j = base + tid;
+        const int x = j < k ? tot[j] : 0;
+        int incl = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o);
+            if (lane >= o) incl += y;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        int wpre = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int v = wsum[w];
+            wpre += w < wave ? v : 0;
+            all += v;
+        }
+        const int start = carry + wpre + incl - x;
+        if (j < k) {
+            tot[j] = start;
+            if (slice == 0) {
+                sbase[j] = start / P + j;
+                snum[j] = x > 0 ? (start + x - 1) / P - start / P + 1 : 0;
+                if (x > 0 && start + x == b) pad_lists(perm, alpha_s, key_s, b, j);      // j owns the end of the list
+            }
+        }
+        carry += all;
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (key[c] < k) {
+            const int pos = tot[key[c]] + atomicAdd(&wh[wave * k + key[c]], 1);
+            perm[pos] = i0 + c;
+            alpha_s[pos] = alpha[i0 + c];
+            key_s[pos] = key[c];
+        }
     }
 }
 
@@ -140,59 +327,79 @@ template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
     static __device__ __forceinline__ int chunk_of(int grp, int lane, int mch) { return min(2 * (grp * 64 + lane), mch - 1); }
 };
 
-template <typename TR>
-__global__ __launch_bounds__(64) void k_contract(const u32x4_t* __restrict__ dY, const int32_t* __restrict__ perm,
-                                                 const float* __restrict__ alpha_s, const int32_t* __restrict__ key_s, int b,
-                                                 int P, int mch, int m, int cg, float* __restrict__ partial) {
-    const int chunk = blockIdx.x / cg, grp = blockIdx.x % cg;
+// Workgroup = 4 waves that share a chunk of the list and sit side by side along the row: wave w covers W
+// consecutive 512-column groups, so the workgroup reads 4*W KiB of every row at (nearly) the same time.
+template <typename TR, int W>
+__global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const int32_t* __restrict__ perm,
+                                                  const float* __restrict__ alpha_s, const int32_t* __restrict__ key_s, int b,
+                                                  int P, int mch, int m, int wgcols, float* __restrict__ partial) {
+    const int chunk = blockIdx.x / wgcols, wc = blockIdx.x % wgcols;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int grp0 = (wc * 4 + wave) * W;
+    if (grp0 * 512 >= m) return;                           // this wave has no columns (uniform per wave)
     const int s0 = chunk * P;
     const int s1 = min(b, s0 + P);
-    const int lane = threadIdx.x;
-    const int ch = RowLoad<TR>::chunk_of(grp, lane, mch);
-    const int col = grp * 512 + lane * 8;
-
-    float acc[8];
+    int ch[W];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    for (int w = 0; w < W; ++w) ch[w] = RowLoad<TR>::chunk_of(grp0 + w, lane, mch);
+
+    float acc[W][8];
+#pragma unroll
+    for (int w = 0; w < W; ++w)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[w][q] = 0.f;
     int cur = __builtin_amdgcn_readfirstlane(key_s[s0]);
 
     auto flush = [&](int key) {
-        if (col < m) {
-            float4* dst = reinterpret_cast<float4*>(partial + size_t(chunk + key) * m + col);
-            dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            if (col + 4 < m) dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+        for (int w = 0; w < W; ++w) {
+            const int col = (grp0 + w) * 512 + lane * 8;
+            if (col < m) {
+                float4* dst = reinterpret_cast<float4*>(partial + size_t(chunk + key) * m + col);
+                dst[0] = make_float4(acc[w][0], acc[w][1], acc[w][2], acc[w][3]);
+                if (col + 4 < m) dst[1] = make_float4(acc[w][4], acc[w][5], acc[w][6], acc[w][7]);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[w][q] = 0.f;
+        }
     };
 
     // Rows are fetched in groups of U; the next group's loads are issued before the current group is consumed.
-    // Positions past the end of the chunk re-read its last row with weight 0 (no guard around the loads).
-    constexpr int U = RowLoad<TR>::kGroup;
-    auto issue = [&](RowLoad<TR> (&v)[U], float (&a)[U], int (&key)[U], int s) {
+    // The sorted lists are padded to a multiple of 16 entries (weight 0, last key, a valid row), so a group never
+    // needs a guard.
+#ifndef PAMM_CONTRACT_U
+#define PAMM_CONTRACT_U 0
+#endif
+    constexpr int U = PAMM_CONTRACT_U ? PAMM_CONTRACT_U : ((RowLoad<TR>::kGroup / W) < 2 ? 2 : (RowLoad<TR>::kGroup / W));
+    auto issue = [&](RowLoad<TR> (&v)[U][W], float (&a)[U], int (&key)[U], int s) {
+        int row[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int pos = min(s + u, s1 - 1);
-            const int row = __builtin_amdgcn_readfirstlane(perm[pos]);
-            const float al = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[pos])));
-            key[u] = __builtin_amdgcn_readfirstlane(key_s[pos]);
-            a[u] = (s + u < s1) ? al : 0.f;
-            v[u].load(dY + size_t(row) * mch, ch, mch);
+            row[u] = __builtin_amdgcn_readfirstlane(perm[s + u]);
+            a[u] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[s + u])));
+            key[u] = __builtin_amdgcn_readfirstlane(key_s[s + u]);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int w = 0; w < W; ++w) v[u][w].load(dY + size_t(row[u]) * mch, ch[w], mch);
     };
-    auto consume = [&](const RowLoad<TR> (&v)[U], const float (&a)[U], const int (&key)[U]) {
+    auto consume = [&](const RowLoad<TR> (&v)[U][W], const float (&a)[U], const int (&key)[U]) {
         if (key[0] == cur && key[U - 1] == cur) {          // the list is sorted: the whole group belongs to `cur`
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u].fma(a[u], acc);
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int w = 0; w < W; ++w) v[u][w].fma(a[u], acc[w]);
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (key[u] != cur) { flush(cur); cur = key[u]; }
-                v[u].fma(a[u], acc);
+#pragma unroll
+                for (int w = 0; w < W; ++w) v[u][w].fma(a[u], acc[w]);
             }
         }
     };
-    RowLoad<TR> va[U], vb[U];
+    RowLoad<TR> va[U][W], vb[U][W];
     float aa[U], ab[U];
     int ka[U], kb[U];
     issue(va, aa, ka, s0);
@@ -224,30 +431,23 @@ __global__ __launch_bounds__(256) void k_piece_sum(const float* __restrict__ par
 // ------------------------------------------------------------------------------------------------
 // k_prep: puts both operands of C^T Btilde into the layout the MFMA wants, generator index contiguous:
 //   Bt[c][j] = Btilde_j[c] = sum of generator j's pieces (rounded once to bf16 for bf16 inputs), Ct[l][j] = C_j[l],
-// rows padded with zeros to KP generators (a whole number of MFMA steps).  One thread per 16-byte chunk.
-template <typename TR> struct PackChunk;
-template <> struct PackChunk<Bf16> {
-    static __device__ __forceinline__ u32x4_t from_floats(const float (&v)[8]) {
+// rows padded with zeros to KP generators (a multiple of 16).  A workgroup transposes a tile of 64 columns x 16
+// generators through LDS: reads run along the columns (coalesced), writes are whole 16-byte chunks.
+template <typename TR> struct PrepIo;
+template <> struct PrepIo<Bf16> {
+    static constexpr int kChunksPer16 = 2;       // 16 generators = 2 chunks of 8 bf16
+    static __device__ __forceinline__ float load_c(const void* C, size_t idx) {
+        return __uint_as_float(uint32_t(static_cast<const uint16_t*>(C)[idx]) << 16);
+    }
+    static __device__ __forceinline__ u32x4_t pack(const float* v) {     // 8 values
         return u32x4_t{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
     }
-    static __device__ __forceinline__ u32x4_t gather_c(const void* C, size_t n, int l, int j0, int k) {
-        const uint16_t* c = static_cast<const uint16_t*>(C);
-        uint32_t e[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) e[q] = (j0 + q < k) ? uint32_t(c[size_t(j0 + q) * n + l]) : 0u;
-        return u32x4_t{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-    }
 };
-template <> struct PackChunk<F32> {
-    static __device__ __forceinline__ u32x4_t from_floats(const float (&v)[4]) {
+template <> struct PrepIo<F32> {
+    static constexpr int kChunksPer16 = 4;       // 16 generators = 4 chunks of 4 fp32
+    static __device__ __forceinline__ float load_c(const void* C, size_t idx) { return static_cast<const float*>(C)[idx]; }
+    static __device__ __forceinline__ u32x4_t pack(const float* v) {     // 4 values
         return u32x4_t{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
-    }
-    static __device__ __forceinline__ u32x4_t gather_c(const void* C, size_t n, int l, int j0, int k) {
-        const uint32_t* c = static_cast<const uint32_t*>(C);
-        uint32_t e[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) e[q] = (j0 + q < k) ? c[size_t(j0 + q) * n + l] : 0u;
-        return u32x4_t{e[0], e[1], e[2], e[3]};
     }
 };
 
@@ -255,27 +455,38 @@ template <typename TR>
 __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const float* __restrict__ partial,
                                               const int32_t* __restrict__ sbase, const int32_t* __restrict__ snum, int n, int m,
                                               int k, int KC, int blocks_m, u32x4_t* __restrict__ Ct, u32x4_t* __restrict__ Bt) {
-    constexpr int JPC = TR::kPerChunk;
-    const int jg = blockIdx.y, j0 = jg * JPC;
-    if (int(blockIdx.x) < blocks_m) {
-        const int c = blockIdx.x * 256 + threadIdx.x;
-        if (c >= m) return;
-        float v[JPC];
+    __shared__ float tile[64][17];
+    const int tid = threadIdx.x;
+    const int j0 = blockIdx.y * 16;
+    const bool is_b = int(blockIdx.x) < blocks_m;
+    const int x0 = (is_b ? blockIdx.x : blockIdx.x - blocks_m) * 64;      // first column (of dY) or hidden index
+    const int extent = is_b ? m : n;
 #pragma unroll
-        for (int q = 0; q < JPC; ++q) {
-            float s = 0.f;
-            const int j = j0 + q;
-            if (j < k) {                                   // uniform
+    for (int i = 0; i < 4; ++i) {
+        const int pair = tid + 256 * i;
+        const int xx = pair & 63, jj = pair >> 6;                        // jj is the same for a whole wave
+        const int x = x0 + xx, j = j0 + jj;
+        float v = 0.f;
+        if (j < k && x < extent) {
+            if (is_b) {
                 const int base = sbase[j], np = snum[j];
-                for (int t = 0; t < np; ++t) s += partial[size_t(base + t) * m + c];
+                for (int t = 0; t < np; ++t) v += partial[size_t(base + t) * m + x];
+            } else {
+                v = PrepIo<TR>::load_c(C, size_t(j) * n + x);
             }
-            v[q] = s;
         }
-        Bt[size_t(c) * KC + jg] = PackChunk<TR>::from_floats(v);
-    } else {
-        const int l = (blockIdx.x - blocks_m) * 256 + threadIdx.x;
-        if (l >= n) return;
-        Ct[size_t(l) * KC + jg] = PackChunk<TR>::gather_c(C, size_t(n), l, j0, k);
+        tile[xx][jj] = v;
+    }
+    __syncthreads();
+    constexpr int CP = PrepIo<TR>::kChunksPer16;
+    if (tid < 64 * CP) {
+        const int xx = tid & 63, part = tid >> 6;
+        const int x = x0 + xx;
+        if (x < extent) {
+            u32x4_t out = PrepIo<TR>::pack(&tile[xx][part * TR::kPerChunk]);
+            u32x4_t* dst = is_b ? Bt : Ct;
+            dst[size_t(x) * KC + blockIdx.y * CP + part] = out;
+        }
     }
 }
 
@@ -335,7 +546,7 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct GradBuffers {
-    int32_t *perm, *key, *sbase, *snum;
+    int32_t *perm, *key, *sbase, *snum, *table;
     float *alpha_s, *partial;
     u32x4_t *ct, *bt;
 };
@@ -347,6 +558,7 @@ static GradBuffers carve(const GradPlan& pl, char* ws) {
     g.key = reinterpret_cast<int32_t*>(ws + pl.off_key);
     g.sbase = reinterpret_cast<int32_t*>(ws + pl.off_sbase);
     g.snum = reinterpret_cast<int32_t*>(ws + pl.off_snum);
+    g.table = reinterpret_cast<int32_t*>(ws + pl.off_table);
     g.partial = reinterpret_cast<float*>(ws + pl.off_partial);
     g.ct = reinterpret_cast<u32x4_t*>(ws + pl.off_ct);
     g.bt = reinterpret_cast<u32x4_t*>(ws + pl.off_bt);
@@ -358,25 +570,46 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
                                   int b, int k, int m, hipStream_t s) {
     {
         ScopedSpan span(kGroup, s);
-        hipLaunchKernelGGL(k_group, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, g.perm, g.alpha_s, g.key, g.sbase,
-                           g.snum);
+        if (k <= kScatterMaxK) {
+            const int nslices = (b + kSliceRows - 1) / kSliceRows;
+            hipLaunchKernelGGL(k_hist, dim3(nslices), dim3(1024), size_t(k) * 4, s, f, b, k, g.table);
+            hipLaunchKernelGGL(k_scatter, dim3(nslices), dim3(1024), size_t(17) * k * 4, s, f, alpha, b, k, pl.piece_rows, nslices,
+                               g.table, g.perm, g.alpha_s, g.key, g.sbase, g.snum);
+        } else {
+#define PAMM_LAUNCH_GROUP(KERNEL) \
+    hipLaunchKernelGGL(KERNEL, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, g.perm, g.alpha_s, g.key, g.sbase, g.snum)
+        const int nv = (b + 4095) / 4096;      // int4 loads per lane when 16 waves share the rows
+        if (nv <= 1) PAMM_LAUNCH_GROUP(k_group_regs<1>);
+        else if (nv <= 2) PAMM_LAUNCH_GROUP(k_group_regs<2>);
+        else if (nv <= 4) PAMM_LAUNCH_GROUP(k_group_regs<4>);
+        else if (nv <= 8) PAMM_LAUNCH_GROUP(k_group_regs<8>);
+        else if (nv <= 16) PAMM_LAUNCH_GROUP(k_group_regs<16>);
+        else PAMM_LAUNCH_GROUP(k_group_stream);
+#undef PAMM_LAUNCH_GROUP
+        }
     }
     const int mch = m / TR::kPerChunk;
     {
         ScopedSpan span(kContract, s);
-        hipLaunchKernelGGL((k_contract<TR>), dim3((unsigned)(pl.chunks * pl.col_groups)), dim3(64), 0, s, (const u32x4_t*)dY, g.perm,
-                           g.alpha_s, g.key, b, pl.piece_rows, mch, m, pl.col_groups, g.partial);
+        const dim3 grid((unsigned)(pl.chunks * pl.wg_cols));
+#define PAMM_LAUNCH_CONTRACT(WV) \
+    hipLaunchKernelGGL((k_contract<TR, WV>), grid, dim3(256), 0, s, (const u32x4_t*)dY, g.perm, g.alpha_s, g.key, b, pl.piece_rows, \
+                       mch, m, pl.wg_cols, g.partial)
+        if (pl.wave_groups == 1) PAMM_LAUNCH_CONTRACT(1);
+        else if (pl.wave_groups == 2) PAMM_LAUNCH_CONTRACT(2);
+        else PAMM_LAUNCH_CONTRACT(3);
+#undef PAMM_LAUNCH_CONTRACT
     }
 }
 
 template <typename TR>
 static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void* C, int n, int m, int k, float* dW, hipStream_t s) {
     const int KC = int(pl.kpad) / TR::kPerChunk;
-    const int blocks_m = (m + 255) / 256, blocks_n = (n + 255) / 256;
+    const int blocks_m = (m + 63) / 64, blocks_n = (n + 63) / 64;
     {
         ScopedSpan span(kPrep, s);
-        hipLaunchKernelGGL((k_prep<TR>), dim3((unsigned)(blocks_m + blocks_n), (unsigned)KC), dim3(256), 0, s, C, g.partial, g.sbase,
-                           g.snum, n, m, k, KC, blocks_m, g.ct, g.bt);
+        hipLaunchKernelGGL((k_prep<TR>), dim3((unsigned)(blocks_m + blocks_n), (unsigned)(pl.kpad / 16)), dim3(256), 0, s, C,
+                           g.partial, g.sbase, g.snum, n, m, k, KC, blocks_m, g.ct, g.bt);
     }
     const int tiles_n = (n + 127) / 128, tiles_m = (m + 127) / 128;
     {

@@ -10,6 +10,7 @@
 namespace pamm {
 
 constexpr int64_t kMaxGenerators = 16384;
+constexpr int64_t kNumCU = 256;            // compute units of the MI355X
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -20,7 +21,9 @@ inline bool dtype_ok(pamm_dtype dt) { return dt == PAMM_F32 || dt == PAMM_BF16; 
 
 // Tuning overrides for experiments (read on every call; unset or invalid = use the built-in heuristic):
 //   PAMM_SCORE_TT    token fragments per wave in k_score (1 or 2)
+//   PAMM_SCORE_NW    waves per workgroup in k_score when PAMM_SCORE_TT is 1 (2, 4 or 8)
 //   PAMM_PIECE_ROWS  list positions per chunk in k_contract (a multiple of 16, 16..4096)
+//   PAMM_CONTRACT_W  512-column groups per wave in k_contract (1..3)
 inline int env_int(const char* name) {
     const char* v = getenv(name);
     return v ? atoi(v) : 0;
@@ -30,7 +33,8 @@ inline int env_int(const char* name) {
 
 struct CompressPlan {
     int tg;          // 32-generator fragments per wave (1, 2, 4 or 8): a column block holds 32*tg generators
-    int tt;          // 32-token fragments per wave (1 or 2): a workgroup of 4 waves holds 128*tt tokens
+    int tt;          // 32-token fragments per wave (1 or 2)
+    int nw;          // waves per workgroup (2, 4 or 8; 4 when tt = 2): a workgroup holds 32*tt*nw tokens
     int ncb;         // column blocks = ceil(k / (32*tg))
     int64_t row_tiles;
     // workspace offsets (bytes)
@@ -46,12 +50,22 @@ inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt,
     while (tg < 8 && 32 * tg < k) tg *= 2;
     p->tg = tg;
     p->ncb = int((k + 32 * tg - 1) / (32 * tg));
-    // two token fragments per wave halve the LDS reads per MFMA; use them once the grid still covers the chip
-    int64_t tiles2 = (b + 255) / 256;
-    p->tt = (tiles2 * p->ncb >= 512) ? 2 : 1;
+    // Memory-bound shapes (k <= 128): one token fragment per wave and as many waves per workgroup as still give
+    // every CU a workgroup.  Compute-bound shapes: two token fragments per wave halve the LDS reads per MFMA.
+    const int64_t tiles256 = (b + 255) / 256;
+    p->tt = (k > 128 && tiles256 * p->ncb >= 192) ? 2 : 1;
     const int tt_env = env_int("PAMM_SCORE_TT");
     if (tt_env == 1 || tt_env == 2) p->tt = tt_env;
-    p->row_tiles = (b + 128 * p->tt - 1) / (128 * p->tt);
+    if (p->tt == 2) {
+        p->nw = 4;
+    } else {
+        p->nw = 8;
+        while (p->nw > 2 && ((b + 32 * p->nw - 1) / (32 * p->nw)) * p->ncb < 224) p->nw /= 2;
+        const int nw_env = env_int("PAMM_SCORE_NW");
+        if (nw_env == 2 || nw_env == 4 || nw_env == 8) p->nw = nw_env;
+    }
+    const int64_t tile_tokens = 32 * p->tt * p->nw;
+    p->row_tiles = (b + tile_tokens - 1) / tile_tokens;
     size_t o = 0;
     p->off_idx = o;  o = align_up(o + size_t(k) * 4, 256);
     p->off_inv = o;  o = align_up(o + size_t(k) * 4, 256);
@@ -68,9 +82,11 @@ struct GradPlan {
     int piece_rows;       // P: the sorted row list is cut into chunks of P positions (a multiple of 16)
     int64_t chunks;       // ceil(b / P)
     int64_t nslots;       // upper bound on piece numbers: chunks + k
-    int col_groups;       // ceil(m / 512): one wave covers 512 columns of a row
-    int64_t kpad;         // k rounded up to a whole number of MFMA steps (16 generators for bf16, 8 for fp32)
-    size_t off_perm, off_alpha, off_key, off_sbase, off_snum, off_partial, off_ct, off_bt, total;
+    int col_groups;       // ceil(m / 512)
+    int wave_groups;      // W: 512-column groups per wave (1..3); a workgroup of 4 waves covers 4*W groups of a row
+    int wg_cols;          // workgroups side by side along a row: ceil(col_groups / (4*W))
+    int64_t kpad;         // k rounded up to a multiple of 16 (a whole number of MFMA steps for both element types)
+    size_t off_perm, off_alpha, off_key, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
 };
 
 inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, GradPlan* p) {
@@ -80,9 +96,16 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     if (k > kMaxGenerators) return PAMM_ERR_UNSUPPORTED;
     if (n % per_chunk(dt) != 0 || m % per_chunk(dt) != 0) return PAMM_ERR_UNSUPPORTED;
     p->col_groups = int((m + 511) / 512);
-    // One wave per (chunk, column group).  All waves carry the same load, so the best grid is a single round
-    // that fits the chip: ~14 waves per CU (16 fit at the kernel's register count).
-    int64_t P = (b * p->col_groups + 3583) / 3584;
+    int W = (p->col_groups + 3) / 4;
+    W = W < 1 ? 1 : (W > 3 ? 3 : W);
+    const int w_env = env_int("PAMM_CONTRACT_W");
+    if (w_env >= 1 && w_env <= 3) W = w_env;
+    p->wave_groups = W;
+    p->wg_cols = (p->col_groups + 4 * W - 1) / (4 * W);
+    // One workgroup per (chunk, 4*W column groups).  All workgroups carry the same load, and measured on the
+    // MI355X the contraction runs best as one even round: exactly one workgroup per CU (256 CUs), i.e. few, long
+    // chunks (4 waves per CU, each with >= 12 KiB of dY in flight).
+    int64_t P = (b * p->wg_cols + kNumCU - 1) / kNumCU;
     P = (P + 15) / 16 * 16;
     if (P < 16) P = 16;
     if (P > 4096) P = 4096;
@@ -91,14 +114,14 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     p->piece_rows = int(P);
     p->chunks = (b + P - 1) / P;
     p->nslots = p->chunks + k;
-    const int64_t step = 2 * per_chunk(dt);
-    p->kpad = (k + step - 1) / step * step;
+    p->kpad = (k + 15) / 16 * 16;
     size_t o = 0;
-    p->off_perm = o;    o = align_up(o + size_t(b) * 4, 256);
-    p->off_alpha = o;   o = align_up(o + size_t(b) * 4, 256);
-    p->off_key = o;     o = align_up(o + size_t(b) * 4, 256);
+    p->off_perm = o;    o = align_up(o + size_t(b + 16) * 4, 256);      // the sorted lists are padded to a multiple of 16
+    p->off_alpha = o;   o = align_up(o + size_t(b + 16) * 4, 256);
+    p->off_key = o;     o = align_up(o + size_t(b + 16) * 4, 256);
     p->off_sbase = o;   o = align_up(o + size_t(k) * 4, 256);
     p->off_snum = o;    o = align_up(o + size_t(k) * 4, 256);
+    p->off_table = o;   o = align_up(o + size_t((b + 4095) / 4096) * size_t(k) * 4, 256);    // per-slice histograms
     p->off_partial = o; o = align_up(o + size_t(p->nslots) * size_t(m) * 4, 256);
     p->off_ct = o;      o = align_up(o + size_t(n) * size_t(p->kpad) * elem_bytes(dt), 256);
     p->off_bt = o;      o = align_up(o + size_t(m) * size_t(p->kpad) * elem_bytes(dt), 256);

@@ -122,6 +122,9 @@ SMALL = [
     ("bf16_k1", "llama60m", dict(seqs=1, seq_len=130, n=64, m=128, k=1, centres=4)),
     ("f32_k1", "tiny", dict(seqs=1, seq_len=65, n=36, m=44, k=1, centres=4)),
     ("bf16_one_row", "llama60m", dict(seqs=1, seq_len=1, n=8, m=8, k=1, centres=1)),
+    ("bf16_many_rows", "llama60m", dict(seqs=7, seq_len=10001, n=16, m=24, k=3, centres=6)),   # b > 65536: streaming grouping path
+    ("f32_k17_pad16", "tiny", dict(seqs=2, seq_len=97, n=44, m=36, k=17, centres=20)),
+    ("bf16_k2500_per_generator_grouping", "llama1b", dict(seqs=3, seq_len=1000, n=32, m=40, k=2500, centres=3000)),
 ]
 
 
@@ -136,7 +139,7 @@ def test_small_shapes(pamm, oracle, name, base, over):
 def test_all_rows_as_generators_reproduces_exact_product(pamm, oracle, dtype_name):
     """k = b: every row is its own generator with alpha = 1, so dW is X^T dY (the plain product)."""
     base = "tiny" if dtype_name == "f32" else "llama1b"          # recipes without padding copies
-    w = workloads.scaled(workloads.WORKLOADS[base], seqs=2, seq_len=256, n=64, m=96, k=512, centres=512)
+    w = workloads.scaled(workloads.WORKLOADS[base], seqs=8, seq_len=256, n=64, m=96, k=2048, centres=2048)
     X, dY = workloads.generate(w)
     ora, got = run_case(pamm, oracle, X, dY, w.k, w.dtype, label=f"k=b {dtype_name}")
     exact = oracle.to_f64(X).T @ oracle.to_f64(dY)
