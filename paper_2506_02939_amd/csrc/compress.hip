@@ -332,6 +332,10 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     static_assert(NW * 32 * SROW * sizeof(float) <= sizeof(lds_raw), "score dump does not fit");
     float* sdump = reinterpret_cast<float*>(lds_raw) + wave * (32 * SROW);
     const float kClose = 1.f - 0x1p-12f;
+#if defined(PAMM_DBG_NOEPI)
+    if (acc[0][0][0] == 123.456f) cand[tid] = u32x4_t{1u, 2u, 3u, 4u};
+    return;
+#endif
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         auto dump = [&](int h) {                 // scores of pass h -> this wave's LDS tile, [token][generator]
@@ -401,29 +405,41 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
             best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
             if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
         } else {
-            // Round 2 (rare): the complete four-value record for the whole wave
+            // Round 2 (few waves): now that the winner is known, list the distinct scores within 2^-12 of it.
+            // Only those can matter to k_finalize, and they are rare, so the scan is one compare per generator
+            // with an insertion when a lane finds one.
             Best best;
             best.init();
+            best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
+            const float thr = m1 * kClose;
 #pragma unroll
             for (int h = 0; h < TG / PF; ++h) {
                 dump(h);
                 const int jl0 = h * PG + g * (PG / 2);
-#pragma unroll 1
+#pragma unroll 2
                 for (int c = 0; c < PG / 2; c += 4) {
                     const float4 d4 = *reinterpret_cast<const float4*>(&srow[c]);
                     const float4 iv4 = *reinterpret_cast<const float4*>(&lds_inv[jl0 + c]);
                     const float dd[4] = {d4.x, d4.y, d4.z, d4.w}, iv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (iv[e] >= 0.f) best.push(dd[e] * dd[e] * iv[e], gen0 + jl0 + c + e, dd[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        const float sc = iv[e] >= 0.f ? dd[e] * dd[e] * iv[e] : -3.f;
+                        const bool hit = close && sc >= thr && sc < m1;
+                        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+                            if (hit) best.insert_lower(sc, gen0 + jl0 + c + e);
+                        }
+                    }
                 }
                 wave_lds_sync();
             }
-            Best o;
-            o.s1 = __shfl_xor(best.s1, 32); o.j1 = __shfl_xor(best.j1, 32); o.d1 = __shfl_xor(best.d1, 32);
-            o.jt = __shfl_xor(best.jt, 32); o.s2 = __shfl_xor(best.s2, 32); o.j2 = __shfl_xor(best.j2, 32);
-            o.s3 = __shfl_xor(best.s3, 32); o.j3 = __shfl_xor(best.j3, 32); o.s4 = __shfl_xor(best.s4, 32);
-            best.merge(o);
+            // join the two halves of the token: both lanes hold the same winner, only the close values differ
+            {
+                const float o2 = __shfl_xor(best.s2, 32), o3 = __shfl_xor(best.s3, 32), o4 = __shfl_xor(best.s4, 32);
+                const int p2 = __shfl_xor(best.j2, 32), p3 = __shfl_xor(best.j3, 32);
+                best.insert_lower(o2, p2);
+                best.insert_lower(o3, p3);
+                if (o4 < best.s3 && o4 > best.s4) best.s4 = o4;
+            }
             if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
         }
     }

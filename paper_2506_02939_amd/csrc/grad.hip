@@ -193,7 +193,7 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
 // Inside a wave the order of equal keys is the order in which the LDS unit serves the lanes of one atomic
 // instruction; it does not depend on timing, so the list, and every sum formed from it, is the same on every call.
 constexpr int kSliceRows = 4096;
-constexpr int kScatterMaxK = 2048;
+constexpr int kScatterMaxK = 2048;     // 18 * k ints of LDS
 
 __global__ __launch_bounds__(1024) void k_hist(const int32_t* __restrict__ f, int b, int k, int32_t* __restrict__ table) {
     extern __shared__ int hist[];
@@ -218,11 +218,12 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
     extern __shared__ int lds[];
     int* wh = lds;                 // [16][k]  per-wave counts, later per-wave next free position inside the generator's list
     int* tot = lds + 16 * k;       // [k]      rows per generator (whole batch), later start of the generator's list
+    int* bef = lds + 17 * k;       // [k]      rows per generator in earlier slices
     __shared__ int wsum[16];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int slice = blockIdx.x;
 
-    for (int q = tid; q < 16 * k; q += 1024) wh[q] = 0;
+    for (int q = tid; q < 18 * k; q += 1024) wh[q] = 0;      // wh, tot and bef are contiguous
     __syncthreads();
     int key[4];
     const int i0 = slice * kSliceRows + 4 * tid;      // wave w owns rows [256 w, 256 w + 256) of the slice
@@ -232,21 +233,34 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
         if (key[c] < k) atomicAdd(&wh[wave * k + key[c]], 1);
     __syncthreads();
 
-    for (int j = tid; j < k; j += 1024) {
-        int before = 0, total = 0;
-        for (int s = 0; s < nslices; ++s) {
-            const int c = table[size_t(s) * k + j];
-            before += s < slice ? c : 0;
-            total += c;
+    // rows of every generator in earlier slices / in all slices: column sums of the table, taken in parallel by all
+    // threads (each sums a strip of slices for one generator), then folded through LDS
+    {
+        const int strips = k <= 1024 ? 1024 / max(k, 1) : 1;        // threads per generator (power-of-two k: exact)
+        for (int j0 = 0; j0 < k; j0 += 1024) {
+            const int j = j0 + (strips > 1 ? tid % k : tid);
+            const int strip = strips > 1 ? tid / k : 0;
+            int before = 0, total = 0;
+            if (j < k && strip < strips) {
+                for (int s = strip; s < nslices; s += strips) {
+                    const int c = table[size_t(s) * k + j];
+                    before += s < slice ? c : 0;
+                    total += c;
+                }
+                atomicAdd(&tot[j], total);           // tot and bef start at zero (cleared with wh below)
+                atomicAdd(&bef[j], before);
+            }
         }
-        int run = before;
+    }
+    __syncthreads();
+    for (int j = tid; j < k; j += 1024) {
+        int run = bef[j];
 #pragma unroll
         for (int w = 0; w < 16; ++w) {
             const int c = wh[w * k + j];
             wh[w * k + j] = run;
             run += c;
         }
-        tot[j] = total;
     }
     __syncthreads();
 
@@ -470,7 +484,13 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
         if (j < k && x < extent) {
             if (is_b) {
                 const int base = sbase[j], np = snum[j];
-                for (int t = 0; t < np; ++t) v += partial[size_t(base + t) * m + x];
+                for (int t = 0; t < np; t += 4) {          // four pieces in flight; slots past the last one re-read it with weight 0
+                    float p4[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) p4[q] = partial[size_t(base + min(t + q, np - 1)) * m + x];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v += (t + q < np) ? p4[q] : 0.f;
+                }
             } else {
                 v = PrepIo<TR>::load_c(C, size_t(j) * n + x);
             }
@@ -573,7 +593,7 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
         if (k <= kScatterMaxK) {
             const int nslices = (b + kSliceRows - 1) / kSliceRows;
             hipLaunchKernelGGL(k_hist, dim3(nslices), dim3(1024), size_t(k) * 4, s, f, b, k, g.table);
-            hipLaunchKernelGGL(k_scatter, dim3(nslices), dim3(1024), size_t(17) * k * 4, s, f, alpha, b, k, pl.piece_rows, nslices,
+            hipLaunchKernelGGL(k_scatter, dim3(nslices), dim3(1024), size_t(18) * k * 4, s, f, alpha, b, k, pl.piece_rows, nslices,
                                g.table, g.perm, g.alpha_s, g.key, g.sbase, g.snum);
         } else {
 #define PAMM_LAUNCH_GROUP(KERNEL) \
