@@ -203,6 +203,14 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 
     const int nstages = (nch + CPS - 1) / CPS;
     const int nss = (nch + 7) / 8;               // super-steps
+    // Every workgroup walks the hidden dimension from a different starting window and wraps around (a dot product
+    // does not care where it starts).  Without this all workgroups sit at the same column of their rows at the same
+    // time, and since rows are a power of two apart the whole chip then leans on a few memory channels.
+    const int rot = (rt * 5) % nss;
+    auto turned = [&](int v) {                   // walk position -> window of the row; positions past the end repeat the last
+        const int a = min(v, nss - 1) + rot;
+        return a >= nss ? a - nss : a;
+    };
 
     u32x4_t creg[CLOADS];
     auto load_c = [&](int stage) {
@@ -210,7 +218,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         for (int i = 0; i < CLOADS; ++i) {
             const int q = tid + NT * i;
             const int row = q / CPS, cc = q % CPS;
-            const int j = gen0 + row, c = stage * CPS + cc;
+            const int j = gen0 + row, c = turned(stage * SS + cc / 8) * 8 + (cc & 7);
             // Clamped addresses, no guard and no mask: a guarded load costs a branch per chunk, and a mask makes
             // the compiler wait for the load where it is issued.  Rows past the last generator are ignored by
             // the epilogue; chunks past the end of a row meet zero chunks of X.
@@ -238,10 +246,10 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 #if defined(PAMM_DBG_NOX)
                     dst[tt][i] = u32x4_t{uint32_t(sstep), 1u, 2u, 3u};
 #else
-                    dst[tt][i] = xrow[tt][i][min(sstep, nss - 1) * 8 + xchunk];
+                    dst[tt][i] = xrow[tt][i][turned(sstep) * 8 + xchunk];
 #endif
                 } else {
-                    const int c = sstep * 8 + xchunk;
+                    const int c = turned(sstep) * 8 + xchunk;
                     const uint32_t keep = c < nch ? 0xffffffffu : 0u;
                     dst[tt][i] = xrow[tt][i][min(c, nch - 1)] & keep;
                 }
