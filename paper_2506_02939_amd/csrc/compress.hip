@@ -1,11 +1,12 @@
 // pamm_compress / pamm_compress_idx: Alg. 1, procedure Compress, at eps = infinity.
 //
-// Three launches on the caller's stream:
+// Launches on the caller's stream:
 //   k_gather    C_j = X[idx_j] (bit copy), ||C_j||^2 in fp64, a content hash per generator
 //   k_score     streams X once; D = C X^T on the matrix cores with C staged through LDS, then per token the
-//               three largest distinct values of s(i,j) = <X_i,C_j>^2/||C_j||^2 (Lemma 1) and where they occur
-//   k_finalize  merges column blocks, writes f and alpha (Eq. 1), and re-decides in fp64 the few rows whose
-//               leading scores are too close for fp32 to separate
+//               largest values of s(i,j) = <X_i,C_j>^2/||C_j||^2 (Lemma 1) and where they occur.  With up to 256
+//               generators (one column block) it also takes the final decision: f, alpha (Eq. 1), the few rows
+//               whose leading scores are too close for fp32 to separate being re-decided in fp64
+//   k_finalize  only with more than 256 generators: merges the column blocks and takes that final decision
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -125,6 +126,75 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
 }
 
 // ------------------------------------------------------------------------------------------------
+// The final word on f(i) and alpha_i for the (up to 64) tokens held by the lanes of one wave.  Lane-private input:
+// the token's record `st` over ALL generators.  Tokens whose leading scores are within 2^-12 (relative) of each
+// other are re-decided in fp64 by the whole wave, one token at a time: among up to four named candidates when at
+// most three distinct values are that close, among all generators otherwise.  Every lane of the wave must call.
+template <typename TR>
+__device__ __forceinline__ double wave_dot(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ c, int nch, int lane) {
+    double acc = 0.0;
+#pragma unroll 4
+    for (int q = lane; q < nch; q += kWave) {
+        float a[TR::kPerChunk], bq[TR::kPerChunk];
+        TR::unpack(x[q], a);
+        TR::unpack(c[q], bq);
+#pragma unroll
+        for (int e = 0; e < TR::kPerChunk; ++e) acc += double(a[e]) * double(bq[e]);
+    }
+    return wave_sum(acc);
+}
+
+template <typename TR>
+__device__ __forceinline__ void decide_rows(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
+                                            const float* __restrict__ inv, const double* __restrict__ cn2,
+                                            const unsigned long long* __restrict__ hash, int nch, int k, bool valid, int row,
+                                            const Best& st, int& fi, float& al) {
+    const int lane = threadIdx.x & 63;
+    fi = st.j1;
+    al = st.d1 * inv[st.j1];
+    int ncand = 0, c1 = 0, c2 = 0, c3 = 0;     // extra candidates beside j1 (ncand = 4 means "all generators")
+    if (valid && st.s1 > 0.f) {
+        const float thr = st.s1 * (1.f - 0x1p-12f);
+        // an exact tie between two generators whose rows are bit-identical needs no second look: the lower one wins
+        if (st.jt >= 0 &&
+            !(hash[st.j1] == hash[st.jt] && __double_as_longlong(cn2[st.j1]) == __double_as_longlong(cn2[st.jt])))
+            c1 = st.jt, ncand = 1;
+        if (st.s2 >= thr) { (ncand == 0 ? c1 : c2) = st.j2; ++ncand; }
+        if (st.s3 >= thr) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
+        if (st.s4 >= thr) ncand = 4;
+    }
+    unsigned long long pending = __ballot(ncand != 0);
+    while (pending) {
+        const int L = __ffsll((long long)pending) - 1;
+        pending &= pending - 1;
+        const int rrow = __shfl(row, L), rn = __shfl(ncand, L);
+        int cj[4] = {__shfl(st.j1, L), __shfl(c1, L), __shfl(c2, L), __shfl(c3, L)};
+        const u32x4_t* xr = X + size_t(rrow) * nch;
+        double bs = -1.0, bd = 0.0, bc = 1.0;
+        int bj = 0;
+        auto eval = [&](int j) {
+            double d = wave_dot<TR>(xr, C + size_t(j) * nch, nch, lane);
+            double c2n = cn2[j];
+            double sc = c2n > 0.0 ? d * d / c2n : 0.0;
+            if (sc > bs) { bs = sc; bd = d; bc = c2n; bj = j; }       // strict: lowest j keeps a tie
+        };
+        if (rn < 4) {
+            const int cnt = rn + 1;
+            // candidates in increasing j (all values are wave-uniform)
+            for (int a = 1; a < cnt; ++a)
+                for (int q = a; q > 0 && cj[q] < cj[q - 1]; --q) { int t = cj[q]; cj[q] = cj[q - 1]; cj[q - 1] = t; }
+            for (int a = 0; a < cnt; ++a) eval(cj[a]);
+        } else {
+            for (int j = 0; j < k; ++j) eval(j);
+        }
+        if (lane == L) {
+            fi = bj;
+            al = bc > 0.0 ? float(bd / bc) : 0.f;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // k_score.  Workgroup = NW waves; wave w owns 32*TT tokens; the workgroup owns one column block of
 // 32*TG generators.  Roles in the 32x32 MFMA: A operand = generators, B operand = tokens, so a lane
 // ends up holding scores of ONE token (lane%32) against 16*TG generators per token fragment.
@@ -140,17 +210,13 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
 // C: staged through LDS in stages of 64/TG chunks per generator (32 KiB per stage), double buffered; the
 // global loads of stage s+1 are in flight while stage s is consumed.
 // LDS fragments for MFMA step u+1 are requested before the MFMAs of step u are issued.
-#if defined(PAMM_DBG_TIME)
-__device__ unsigned long long g_dbg_time[4 * 4096];
-#define PAMM_STAMP(slot) do { if (lane == 0 && wave == 0 && blockIdx.x < 4096) g_dbg_time[blockIdx.x * 4 + (slot)] = wall_clock64(); } while (0)
-#else
-#define PAMM_STAMP(slot) do { } while (0)
-#endif
-
-template <typename TR, int TG, int TT, int NW, bool ALIGNED>
+// FUSED (one column block holds every generator): the epilogue takes the final decision itself and writes f and
+// alpha; otherwise it writes one candidate record per token and column block for k_finalize.
+template <typename TR, int TG, int TT, int NW, bool ALIGNED, bool FUSED>
 __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                                   const float* __restrict__ inv, int b, int nch, int k, int ncb,
-                                                   u32x4_t* __restrict__ cand) {
+                                                   const float* __restrict__ inv, const double* __restrict__ cn2,
+                                                   const unsigned long long* __restrict__ hash, int b, int nch, int k, int ncb,
+                                                   u32x4_t* __restrict__ cand, int32_t* __restrict__ f, float* __restrict__ alpha) {
     constexpr int NT = 64 * NW;
     constexpr int GB = 32 * TG;          // generators per column block
     constexpr int SS = 8 / TG;           // super-steps per stage
@@ -173,7 +239,6 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     const int rt = blockIdx.x / ncb;
     const int gen0 = cb * GB;
 
-    PAMM_STAMP(0);
     for (int t = tid; t < GB; t += NT) {
         const int j = gen0 + t;
         lds_inv[t] = j < k ? inv[j] : -1.f;        // negative marks a slot past the last generator
@@ -222,11 +287,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
             // Clamped addresses, no guard and no mask: a guarded load costs a branch per chunk, and a mask makes
             // the compiler wait for the load where it is issued.  Rows past the last generator are ignored by
             // the epilogue; chunks past the end of a row meet zero chunks of X.
-#if defined(PAMM_DBG_NOC)
-            creg[i] = u32x4_t{uint32_t(j), uint32_t(c), 2u, 3u};
-#else
             creg[i] = C[size_t(min(j, k - 1)) * nch + min(c, nch - 1)];
-#endif
         }
     };
     auto store_c = [&](int buf) {
@@ -243,11 +304,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (ALIGNED) {        // rows are whole super-steps: clamp the super-step, nothing to mask
-#if defined(PAMM_DBG_NOX)
-                    dst[tt][i] = u32x4_t{uint32_t(sstep), 1u, 2u, 3u};
-#else
                     dst[tt][i] = xrow[tt][i][turned(sstep) * 8 + xchunk];
-#endif
                 } else {
                     const int c = turned(sstep) * 8 + xchunk;
                     const uint32_t keep = c < nch ? 0xffffffffu : 0u;
@@ -269,7 +326,6 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     stash_x(xr[0], 0);
     __syncthreads();
 
-    PAMM_STAMP(1);
     const int nbody = (nss + UN - 1) / UN;
     int buf = 0, stage = 0;
     for (int bi = 0; bi < nbody; ++bi) {
@@ -281,18 +337,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 if (stage + 1 < nstages) load_c(stage + 1);
             }
             load_x(xr[(p + D - 1) % D], gs + D - 1);
-#if defined(PAMM_DBG_NOSTASH)
-            acc[0][0][1] += __uint_as_float(xr[(p + 1) % D][0][0].x ^ xr[(p + 1) % D][0][1].y ^ xr[(p + 1) % D][0][2].z ^ xr[(p + 1) % D][0][3].w);
-#else
             stash_x(xr[(p + 1) % D], (gs + 1) & 1);          // next super-step's tokens into the other slot
-#endif
-#if defined(PAMM_DBG_NOCOMP)
-            if (gs < nss) {
-                const u32x4_t* cbuf = lds_c + buf * CBUF;
-                const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
-                acc[0][0][0] += __uint_as_float(cbuf[tid].x ^ xbuf[lane].y);
-            }
-#else
             if (gs < nss) {                                  // uniform; only false in the tail of the last body
                 const u32x4_t* cbuf = lds_c + buf * CBUF;
                 const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
@@ -313,14 +358,9 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                         for (int tt = 0; tt < TT; ++tt) TR::mma(a[u & 1][tg], bx[u & 1][tt], acc[tg][tt]);
                 }
             }
-#endif
             if (p % SS == SS - 1) {                          // the stage ends: publish the next one
                 if (stage + 1 < nstages) store_c(buf ^ 1);
-#if defined(PAMM_DBG_NOBAR)
-                wave_lds_sync();
-#else
                 __syncthreads();
-#endif
                 buf ^= 1;
             } else {
                 wave_lds_sync();                             // the stashed tokens are read by other lanes of this wave
@@ -332,7 +372,6 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     // The scores go through LDS (all tiles are free after the last barrier) so that the scan over generators
     // is a small rolled loop instead of hundreds of unrolled compare/select chains: each pass dumps PG
     // generators x 32 tokens per wave, then lane (r,g) scans half of them for token r in increasing order.
-    PAMM_STAMP(2);
     constexpr int PFMAX = NW == 8 ? 2 : 4;
     constexpr int PF = TG < PFMAX ? TG : PFMAX;   // fragments per pass
     constexpr int PG = 32 * PF;              // generators per pass
@@ -340,10 +379,6 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     static_assert(NW * 32 * SROW * sizeof(float) <= sizeof(lds_raw), "score dump does not fit");
     float* sdump = reinterpret_cast<float*>(lds_raw) + wave * (32 * SROW);
     const float kClose = 1.f - 0x1p-12f;
-#if defined(PAMM_DBG_NOEPI)
-    if (acc[0][0][0] == 123.456f) cand[tid] = u32x4_t{1u, 2u, 3u, 4u};
-    return;
-#endif
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         auto dump = [&](int h) {                 // scores of pass h -> this wave's LDS tile, [token][generator]
@@ -406,19 +441,14 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         }
         const bool close = m1 > 0.f && m2 >= m1 * kClose;
         const int row = row_base + 32 * tt + r;
-        if (__builtin_amdgcn_ballot_w64(close) == 0ull) {
-            // nobody in this wave has a distinct runner-up within 2^-12: the record is the winner (and its exact ties)
-            Best best;
-            best.init();
-            best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
-            if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
-        } else {
+        Best best;
+        best.init();
+        best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
+        // If nobody in this wave has a distinct runner-up within 2^-12, the record is the winner (and its exact ties).
+        if (__builtin_amdgcn_ballot_w64(close) != 0ull) {
             // Round 2 (few waves): now that the winner is known, list the distinct scores within 2^-12 of it.
-            // Only those can matter to k_finalize, and they are rare, so the scan is one compare per generator
-            // with an insertion when a lane finds one.
-            Best best;
-            best.init();
-            best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
+            // Only those can matter to the final decision, and they are rare, so the scan is one compare per
+            // generator with an insertion when a lane finds one.
             const float thr = m1 * kClose;
 #pragma unroll
             for (int h = 0; h < TG / PF; ++h) {
@@ -448,28 +478,23 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 best.insert_lower(o3, p3);
                 if (o4 < best.s3 && o4 > best.s4) best.s4 = o4;
             }
+        }
+        if (FUSED) {
+            int fi;
+            float al;
+            decide_rows<TR>(X, C, inv, cn2, hash, nch, k, g == 0 && row < b, row, best, fi, al);
+            if (g == 0 && row < b) {
+                f[row] = fi;
+                alpha[row] = al;
+            }
+        } else {
             if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
         }
     }
-    PAMM_STAMP(3);
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_finalize: one thread per token.
-template <typename TR>
-__device__ __forceinline__ double wave_dot(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ c, int nch, int lane) {
-    double acc = 0.0;
-#pragma unroll 4
-    for (int q = lane; q < nch; q += kWave) {
-        float a[TR::kPerChunk], bq[TR::kPerChunk];
-        TR::unpack(x[q], a);
-        TR::unpack(c[q], bq);
-#pragma unroll
-        for (int e = 0; e < TR::kPerChunk; ++e) acc += double(a[e]) * double(bq[e]);
-    }
-    return wave_sum(acc);
-}
-
+// k_finalize: one thread per token; only needed when the generators span several column blocks.
 template <typename TR>
 __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
                                                   const float* __restrict__ inv, const double* __restrict__ cn2,
@@ -477,7 +502,6 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
                                                   const u32x4_t* __restrict__ cand, int b, int nch, int k, int ncb,
                                                   int32_t* __restrict__ f, float* __restrict__ alpha) {
     const int row = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63;
     const bool valid = row < b;
     Best st;
     st.init();
@@ -488,49 +512,9 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
             if (cb == 0) st = o; else st.merge(o);
         }
     }
-    int fi = st.j1;
-    float al = st.d1 * inv[st.j1];
-    // Rows whose leading scores are within 2^-12 (relative) of each other are re-decided in fp64: among up to four
-    // named candidates when at most three distinct values are that close, among all generators otherwise.
-    int ncand = 0, c1 = 0, c2 = 0, c3 = 0;     // extra candidates beside j1 (ncand = 4 means "all generators")
-    if (valid && st.s1 > 0.f) {
-        const float thr = st.s1 * (1.f - 0x1p-12f);
-        if (st.jt >= 0 &&
-            !(hash[st.j1] == hash[st.jt] && __double_as_longlong(cn2[st.j1]) == __double_as_longlong(cn2[st.jt])))
-            c1 = st.jt, ncand = 1;
-        if (st.s2 >= thr) { (ncand == 0 ? c1 : c2) = st.j2; ++ncand; }
-        if (st.s3 >= thr) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
-        if (st.s4 >= thr) ncand = 4;
-    }
-    unsigned long long pending = __ballot(ncand != 0);
-    while (pending) {
-        const int L = __ffsll((long long)pending) - 1;
-        pending &= pending - 1;
-        const int rrow = __shfl(row, L), rn = __shfl(ncand, L);
-        int cj[4] = {__shfl(st.j1, L), __shfl(c1, L), __shfl(c2, L), __shfl(c3, L)};
-        const u32x4_t* xr = X + size_t(rrow) * nch;
-        double bs = -1.0, bd = 0.0, bc = 1.0;
-        int bj = 0;
-        auto eval = [&](int j) {
-            double d = wave_dot<TR>(xr, C + size_t(j) * nch, nch, lane);
-            double c2n = cn2[j];
-            double s = c2n > 0.0 ? d * d / c2n : 0.0;
-            if (s > bs) { bs = s; bd = d; bc = c2n; bj = j; }       // strict: lowest j keeps a tie
-        };
-        if (rn < 4) {
-            const int cnt = rn + 1;
-            // candidates in increasing j (all values are wave-uniform)
-            for (int a = 1; a < cnt; ++a)
-                for (int q = a; q > 0 && cj[q] < cj[q - 1]; --q) { int t = cj[q]; cj[q] = cj[q - 1]; cj[q - 1] = t; }
-            for (int a = 0; a < cnt; ++a) eval(cj[a]);
-        } else {
-            for (int j = 0; j < k; ++j) eval(j);
-        }
-        if (lane == L) {
-            fi = bj;
-            al = bc > 0.0 ? float(bd / bc) : 0.f;
-        }
-    }
+    int fi;
+    float al;
+    decide_rows<TR>(X, C, inv, cn2, hash, nch, k, valid, row, st, fi, al);
     if (valid) {
         f[row] = fi;
         alpha[row] = al;
@@ -541,35 +525,40 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <typename TR, int TG, int TT, int NW>
-static void launch_score_cfg(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
-                             u32x4_t* cand, hipStream_t s) {
+struct ScoreArgs {
+    const void* X; const void* C; const float* inv; const double* cn2; const unsigned long long* hash;
+    int b, nch, k;
+    u32x4_t* cand; int32_t* f; float* alpha;
+};
+
+template <typename TR, int TG, int TT, int NW, bool FUSED>
+static void launch_score_cfg(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
     dim3 grid((unsigned)(pl.row_tiles * pl.ncb));
-    if (nch % 8 == 0)      // every row is a whole number of 128-byte super-steps
-        hipLaunchKernelGGL((k_score<TR, TG, TT, NW, true>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv,
-                           b, nch, k, pl.ncb, cand);
+    if (a.nch % 8 == 0)      // every row is a whole number of 128-byte super-steps
+        hipLaunchKernelGGL((k_score<TR, TG, TT, NW, true, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
+                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha);
     else
-        hipLaunchKernelGGL((k_score<TR, TG, TT, NW, false>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv,
-                           b, nch, k, pl.ncb, cand);
+        hipLaunchKernelGGL((k_score<TR, TG, TT, NW, false, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
+                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha);
 }
 
-template <typename TR, int TG>
-static void launch_score_tg(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
-                            u32x4_t* cand, hipStream_t s) {
-    if (pl.tt == 2) launch_score_cfg<TR, TG, 2, 4>(pl, X, C, inv, b, nch, k, cand, s);
-    else if (pl.nw == 8) launch_score_cfg<TR, TG, 1, 8>(pl, X, C, inv, b, nch, k, cand, s);
-    else if (pl.nw == 4) launch_score_cfg<TR, TG, 1, 4>(pl, X, C, inv, b, nch, k, cand, s);
-    else launch_score_cfg<TR, TG, 1, 2>(pl, X, C, inv, b, nch, k, cand, s);
+template <typename TR, int TG, bool FUSED>
+static void launch_score_tg(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
+    if (pl.tt == 2) launch_score_cfg<TR, TG, 2, 4, FUSED>(pl, a, s);
+    else if (pl.nw == 8) launch_score_cfg<TR, TG, 1, 8, FUSED>(pl, a, s);
+    else if (pl.nw == 4) launch_score_cfg<TR, TG, 1, 4, FUSED>(pl, a, s);
+    else launch_score_cfg<TR, TG, 1, 2, FUSED>(pl, a, s);
 }
 
+// One column block (k <= 256): the fused kernel.  Several column blocks always use the widest block (TG = 8).
 template <typename TR>
-static void launch_score(const CompressPlan& pl, const void* X, const void* C, const float* inv, int b, int nch, int k,
-                         u32x4_t* cand, hipStream_t s) {
+static void launch_score(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
+    if (pl.ncb > 1) { launch_score_tg<TR, 8, false>(pl, a, s); return; }
     switch (pl.tg) {
-        case 1: launch_score_tg<TR, 1>(pl, X, C, inv, b, nch, k, cand, s); break;
-        case 2: launch_score_tg<TR, 2>(pl, X, C, inv, b, nch, k, cand, s); break;
-        case 4: launch_score_tg<TR, 4>(pl, X, C, inv, b, nch, k, cand, s); break;
-        default: launch_score_tg<TR, 8>(pl, X, C, inv, b, nch, k, cand, s); break;
+        case 1: launch_score_tg<TR, 1, true>(pl, a, s); break;
+        case 2: launch_score_tg<TR, 2, true>(pl, a, s); break;
+        case 4: launch_score_tg<TR, 4, true>(pl, a, s); break;
+        default: launch_score_tg<TR, 8, true>(pl, a, s); break;
     }
 }
 
@@ -589,9 +578,9 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
     }
     {
         ScopedSpan span(kScore, s);
-        launch_score<TR>(pl, X, C, inv, b, nch, k, cand, s);
+        launch_score<TR>(pl, ScoreArgs{X, C, inv, cn2, hash, b, nch, k, cand, f, alpha}, s);
     }
-    {
+    if (pl.ncb > 1) {
         ScopedSpan span(kFinalize, s);
         hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv, cn2,
                            hash, cand, b, nch, k, pl.ncb, f, alpha);
@@ -678,9 +667,3 @@ extern "C" pamm_status pamm_compress(const void* X, int64_t b, int64_t n, int64_
     ring.used[slot] = true;
     return st;
 }
-
-#if defined(PAMM_DBG_TIME)
-extern "C" int pamm_dbg_read_time(unsigned long long* out_host, int count) {
-    return int(hipMemcpyFromSymbol(out_host, HIP_SYMBOL(pamm::g_dbg_time), sizeof(unsigned long long) * count));
-}
-#endif

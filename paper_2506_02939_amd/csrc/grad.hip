@@ -343,6 +343,9 @@ template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
 
 // Workgroup = 4 waves that share a chunk of the list and sit side by side along the row: wave w covers W
 // consecutive 512-column groups, so the workgroup reads 4*W KiB of every row at (nearly) the same time.
+#if defined(PAMM_DBG_TIME)
+__device__ unsigned long long g_dbg_ctime[2 * 4096];
+#endif
 template <typename TR, int W>
 __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const int32_t* __restrict__ perm,
                                                   const float* __restrict__ alpha_s, const int32_t* __restrict__ key_s, int b,
@@ -351,6 +354,9 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp0 = (wc * 4 + wave) * W;
     if (grp0 * 512 >= m) return;                           // this wave has no columns (uniform per wave)
+#if defined(PAMM_DBG_TIME)
+    if (threadIdx.x == 0 && blockIdx.x < 4096) g_dbg_ctime[blockIdx.x * 2] = wall_clock64();
+#endif
     const int s0 = chunk * P;
     const int s1 = min(b, s0 + P);
     int ch[W];
@@ -378,25 +384,34 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
         }
     };
 
-    // Rows are fetched in groups of U; the next group's loads are issued before the current group is consumed.
-    // The sorted lists are padded to a multiple of 16 entries (weight 0, last key, a valid row), so a group never
-    // needs a guard.
+    // Rows are fetched in groups of U, two groups ahead of the one being summed.  Every step of the loop issues
+    // exactly the same number of loads whatever path it takes (positions past the end of the chunk are clamped
+    // onto its last group, which is in cache by then), so the wait before a group's sums only has to cover that
+    // group and the two younger ones stay in flight.  The sorted lists are padded to a multiple of 16 entries
+    // (weight 0, last key, a valid row), so a group never needs a guard.  The row numbers of a group are fetched
+    // one step before its loads are issued.
 #ifndef PAMM_CONTRACT_U
 #define PAMM_CONTRACT_U 0
 #endif
     constexpr int U = PAMM_CONTRACT_U ? PAMM_CONTRACT_U : ((RowLoad<TR>::kGroup / W) < 2 ? 2 : (RowLoad<TR>::kGroup / W));
-    auto issue = [&](RowLoad<TR> (&v)[U][W], float (&a)[U], int (&key)[U], int s) {
-        int row[U];
+    static_assert(16 % (2 * U) == 0, "a chunk must be a whole number of group pairs");
+    const int last = (s1 + 2 * U - 1) / (2 * U) * (2 * U) - U;      // start of the chunk's last group
+    auto rows_of = [&](int (&row)[U], int s) {
+        s = min(s, last);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            row[u] = __builtin_amdgcn_readfirstlane(perm[s + u]);
-            a[u] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[s + u])));
-            key[u] = __builtin_amdgcn_readfirstlane(key_s[s + u]);
-        }
+        for (int u = 0; u < U; ++u) row[u] = __builtin_amdgcn_readfirstlane(perm[s + u]);
+    };
+    auto issue = [&](RowLoad<TR> (&v)[U][W], float (&a)[U], int (&key)[U], const int (&row)[U], int s) {
+        s = min(s, last);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int w = 0; w < W; ++w) v[u][w].load(dY + size_t(row[u]) * mch, ch[w], mch);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[s + u])));
+            key[u] = __builtin_amdgcn_readfirstlane(key_s[s + u]);
+        }
     };
     auto consume = [&](const RowLoad<TR> (&v)[U][W], const float (&a)[U], const int (&key)[U]) {
         if (key[0] == cur && key[U - 1] == cur) {          // the list is sorted: the whole group belongs to `cur`
@@ -415,16 +430,25 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     };
     RowLoad<TR> va[U][W], vb[U][W];
     float aa[U], ab[U];
-    int ka[U], kb[U];
-    issue(va, aa, ka, s0);
+    int ka[U], kb[U], ra[U], rb[U];
+    rows_of(ra, s0);
+    rows_of(rb, s0 + U);
+    issue(va, aa, ka, ra, s0);
+    issue(vb, ab, kb, rb, s0 + U);
+    rows_of(ra, s0 + 2 * U);
+    rows_of(rb, s0 + 3 * U);
     for (int s = s0; s < s1; s += 2 * U) {
-        const bool hb = s + U < s1, ha = s + 2 * U < s1;        // uniform
-        if (hb) issue(vb, ab, kb, s + U);
         consume(va, aa, ka);
-        if (ha) issue(va, aa, ka, s + 2 * U);
-        if (hb) consume(vb, ab, kb);
+        issue(va, aa, ka, ra, s + 2 * U);
+        rows_of(ra, s + 4 * U);
+        consume(vb, ab, kb);
+        issue(vb, ab, kb, rb, s + 3 * U);
+        rows_of(rb, s + 5 * U);
     }
     flush(cur);
+#if defined(PAMM_DBG_TIME)
+    if (threadIdx.x == 0 && blockIdx.x < 4096) g_dbg_ctime[blockIdx.x * 2 + 1] = wall_clock64();
+#endif
 }
 
 // Btilde_j = sum of generator j's partial rows (only used by pamm_contract).
@@ -685,3 +709,9 @@ extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* a
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
+
+#if defined(PAMM_DBG_TIME)
+extern "C" int pamm_dbg_read_ctime(unsigned long long* out_host, int count) {
+    return int(hipMemcpyFromSymbol(out_host, HIP_SYMBOL(pamm::g_dbg_ctime), sizeof(unsigned long long) * count));
+}
+#endif
