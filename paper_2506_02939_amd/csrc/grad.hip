@@ -535,24 +535,58 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_ctb: dW (n x m) = C^T (n x k) * Btilde (k x m).  Workgroup tile 128 x 128, 4 waves of 64 x 64.  Both
-// operands come from k_prep with the generator index contiguous, so every MFMA fragment is one 16-byte
-// load per lane straight from L2/L1 (both operands together are a few MiB): no LDS, no barriers.  The
-// kernel is bound by writing dW.
-template <typename TR>
+// k_ctb: dW (n x m) = C^T (n x k) * Btilde (k x m).  Both operands come from k_prep with the generator index
+// contiguous (Ct[l][j], Bt[c][j]).  Workgroup tile 128 x 128, 4 waves of 64 x 64; the generator index is walked in
+// stages of BK chunks per row (8: 64 bf16 / 32 fp32; 4 when there are few generators, which halves the LDS of a
+// workgroup so that three of them fit a CU and the whole grid is resident at once), staged through LDS with
+// coalesced loads, double buffered, one barrier per stage.  LDS rows are BK+1 chunks apart, which makes the
+// 16-byte reads of a fragment (32 rows, one chunk column) free of bank conflicts.  MFMA step u of a stage takes
+// chunk 2u+g from lane group g, for both operands alike.
+//
+// Tile order: workgroups are handed to the 8 XCDs round-robin, and every XCD has its own L2.  Workgroup number
+// bid therefore takes tile (bid % 8) * ceil(T/8) + bid / 8 of an order that walks the output in strips 8 tiles
+// wide, row by row: the 64 tiles an XCD works on at one time form an 8 x 8 block that shares 8 + 8 operand tiles.
+template <typename TR, int BK>
 __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, const u32x4_t* __restrict__ Bt, int n, int m, int KC,
-                                             int tiles_m, float* __restrict__ dW) {
+                                             int tiles_n, int tiles_m, int per_xcd, float* __restrict__ dW) {
+    constexpr int RS = BK + 1, TILE = 128 * RS;
+    constexpr int SUBS = 256 / BK;               // rows staged per pass of the workgroup
+    constexpr int NI = 128 / SUBS;               // passes per operand tile
+    __shared__ u32x4_t lds[2][2 * TILE];         // [buffer][128 rows of Ct | 128 rows of Bt]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wy = wave >> 1, wx = wave & 1;
-    const int l0 = (blockIdx.x / tiles_m) * 128 + wy * 64, c0 = (blockIdx.x % tiles_m) * 128 + wx * 64;
 
-    const u32x4_t* arow[2];
-    const u32x4_t* brow[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        arow[q] = Ct + size_t(min(l0 + 32 * q + r, n - 1)) * KC + g;
-        brow[q] = Bt + size_t(min(c0 + 32 * q + r, m - 1)) * KC + g;
+    const int L = int(blockIdx.x % 8) * per_xcd + int(blockIdx.x / 8);
+    if (L >= tiles_n * tiles_m) return;          // uniform for the workgroup
+    int tl, tc;
+    {
+        const int full = tiles_m / 8, rem = tiles_m % 8, per_strip = tiles_n * 8;
+        if (L < full * per_strip) { const int q = L % per_strip; tl = q / 8; tc = (L / per_strip) * 8 + q % 8; }
+        else { const int q = L - full * per_strip; tl = q / rem; tc = full * 8 + q % rem; }
     }
+    const int l0 = tl * 128, c0 = tc * 128;
+
+    // staging: thread t moves chunk t%BK of rows t/BK + SUBS*i (i = 0..NI-1) of both operand tiles
+    const int sub = tid / BK, chunk = tid % BK;
+    const u32x4_t* src[2 * NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        src[i] = Ct + size_t(min(l0 + sub + SUBS * i, n - 1)) * KC;
+        src[NI + i] = Bt + size_t(min(c0 + sub + SUBS * i, m - 1)) * KC;
+    }
+    u32x4_t reg[2 * NI];
+    auto gload = [&](int stage) {
+        const int c = stage * BK + chunk;
+        const uint32_t keep = c < KC ? 0xffffffffu : 0u;       // chunks past the last generator count as zeros
+        const int cc = min(c, KC - 1);
+#pragma unroll
+        for (int i = 0; i < 2 * NI; ++i) reg[i] = src[i][cc] & keep;
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2 * NI; ++i) lds[buf][(i < NI ? 0 : TILE) + (sub + SUBS * (i % NI)) * RS + chunk] = reg[i];
+    };
+
     f32x16_t acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -561,25 +595,39 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][bq][i] = 0.f;
 
-#pragma unroll 4
-    for (int t = 0; t < KC; t += 2) {          // one mma call takes chunk t + g from every lane
-        u32x4_t a[2], bq[2];
+    const int nst = (KC + BK - 1) / BK;
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int st = 0; st < nst; ++st) {
+        if (st + 1 < nst) gload(st + 1);
+        const u32x4_t* A = lds[st & 1] + (wy * 64 + r) * RS + g;
+        const u32x4_t* B = lds[st & 1] + TILE + (wx * 64 + r) * RS + g;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) { a[q] = arow[q][t]; bq[q] = brow[q][t]; }
+        for (int u = 0; u < BK / 2; ++u) {
+            u32x4_t a[2], bq[2];
 #pragma unroll
-        for (int fa = 0; fa < 2; ++fa)
+            for (int q = 0; q < 2; ++q) { a[q] = A[32 * q * RS + 2 * u]; bq[q] = B[32 * q * RS + 2 * u]; }
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) TR::mma(a[fa], bq[fb], acc[fa][fb]);
+            for (int fa = 0; fa < 2; ++fa)
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb) TR::mma(a[fa], bq[fb], acc[fa][fb]);
+        }
+        if (st + 1 < nst) sstore((st + 1) & 1);
+        __syncthreads();
     }
 
+    // D layout of the 32x32 MFMA: register i of lane (r,g) is row 8*(i/4)+4*g+(i%4), column r: one store
+    // instruction writes two full 128-byte row segments.
+    const int lw = l0 + wy * 64, cw = c0 + wx * 64;
 #pragma unroll
     for (int fa = 0; fa < 2; ++fa)
 #pragma unroll
         for (int fb = 0; fb < 2; ++fb) {
-            const int c = c0 + 32 * fb + r;
+            const int c = cw + 32 * fb + r;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int l = l0 + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
+                const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
                 if (l < n && c < m) dW[size_t(l) * m + c] = acc[fa][fb][i];
             }
         }
@@ -656,9 +704,15 @@ static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void
                            g.partial, g.sbase, g.snum, n, m, k, KC, blocks_m, g.ct, g.bt);
     }
     const int tiles_n = (n + 127) / 128, tiles_m = (m + 127) / 128;
+    const int per_xcd = (tiles_n * tiles_m + 7) / 8;
     {
         ScopedSpan span(kCtb, s);
-        hipLaunchKernelGGL((k_ctb<TR>), dim3((unsigned)(tiles_n * tiles_m)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_m, dW);
+        if (KC <= 32)     // up to 256 bf16 / 128 fp32 generators: short stages, three workgroups per CU
+            hipLaunchKernelGGL((k_ctb<TR, 4>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_n,
+                               tiles_m, per_xcd, dW);
+        else
+            hipLaunchKernelGGL((k_ctb<TR, 8>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_n,
+                               tiles_m, per_xcd, dW);
     }
 }
 
