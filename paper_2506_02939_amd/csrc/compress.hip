@@ -126,32 +126,40 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
 }
 
 // ------------------------------------------------------------------------------------------------
-// The final word on f(i) and alpha_i for the (up to 64) tokens held by the lanes of one wave.  Lane-private input:
-// the token's record `st` over ALL generators.  Tokens whose leading scores are within 2^-12 (relative) of each
-// other are re-decided in fp64 by the whole wave, one token at a time: among up to four named candidates when at
-// most three distinct values are that close, among all generators otherwise.  Every lane of the wave must call.
+// The final word on f(i) and alpha_i.  A token whose leading scores are within 2^-12 (relative) of each other is
+// re-decided in fp64: among up to four named candidates when at most three distinct values are that close, among
+// all generators otherwise.  Such tokens are rare but unevenly spread, so a workgroup pools them in an LDS queue
+// (decide_or_queue, called by every lane for its token) and its waves then share them out (drain_queue, called by
+// the whole workgroup); one wave re-decides one token at a time, with the rows of all candidates in flight at once.
+constexpr int kRedoInts = 6;     // row, ncand, j1, c1, c2, c3
+
+// dot products of one row of X with two generators, in fp64, by the whole wave.  This code runs a handful of times
+// per launch: it is kept small (rolled loops) because every instruction of it is an instruction-cache miss.
 template <typename TR>
-__device__ __forceinline__ double wave_dot(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ c, int nch, int lane) {
-    double acc = 0.0;
-#pragma unroll 4
-    for (int q = lane; q < nch; q += kWave) {
-        float a[TR::kPerChunk], bq[TR::kPerChunk];
+__device__ __noinline__ void wave_dot2(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ ca, const u32x4_t* __restrict__ cb,
+                                       int nch, double& da, double& db) {
+    double acc0 = 0.0, acc1 = 0.0;
+#pragma unroll 1
+    for (int q = threadIdx.x & 63; q < nch; q += kWave) {
+        float a[TR::kPerChunk], b0[TR::kPerChunk], b1[TR::kPerChunk];
         TR::unpack(x[q], a);
-        TR::unpack(c[q], bq);
+        TR::unpack(ca[q], b0);
+        TR::unpack(cb[q], b1);
 #pragma unroll
-        for (int e = 0; e < TR::kPerChunk; ++e) acc += double(a[e]) * double(bq[e]);
+        for (int e = 0; e < TR::kPerChunk; ++e) {
+            acc0 += double(a[e]) * double(b0[e]);
+            acc1 += double(a[e]) * double(b1[e]);
+        }
     }
-    return wave_sum(acc);
+    da = wave_sum(acc0);
+    db = wave_sum(acc1);
 }
 
+// Called by every lane.  Writes f and alpha of the lane's token unless it needs a second look; then it is queued.
 template <typename TR>
-__device__ __forceinline__ void decide_rows(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                            const float* __restrict__ inv, const double* __restrict__ cn2,
-                                            const unsigned long long* __restrict__ hash, int nch, int k, bool valid, int row,
-                                            const Best& st, int& fi, float& al) {
-    const int lane = threadIdx.x & 63;
-    fi = st.j1;
-    al = st.d1 * inv[st.j1];
+__device__ __forceinline__ void decide_or_queue(const float* __restrict__ inv, const double* __restrict__ cn2,
+                                                const unsigned long long* __restrict__ hash, bool valid, int row, const Best& st,
+                                                int32_t* __restrict__ f, float* __restrict__ alpha, int* q_count, int* q_entries) {
     int ncand = 0, c1 = 0, c2 = 0, c3 = 0;     // extra candidates beside j1 (ncand = 4 means "all generators")
     if (valid && st.s1 > 0.f) {
         const float thr = st.s1 * (1.f - 0x1p-12f);
@@ -163,33 +171,56 @@ __device__ __forceinline__ void decide_rows(const u32x4_t* __restrict__ X, const
         if (st.s3 >= thr) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
         if (st.s4 >= thr) ncand = 4;
     }
-    unsigned long long pending = __ballot(ncand != 0);
-    while (pending) {
-        const int L = __ffsll((long long)pending) - 1;
-        pending &= pending - 1;
-        const int rrow = __shfl(row, L), rn = __shfl(ncand, L);
-        int cj[4] = {__shfl(st.j1, L), __shfl(c1, L), __shfl(c2, L), __shfl(c3, L)};
-        const u32x4_t* xr = X + size_t(rrow) * nch;
+    if (!valid) return;
+    if (ncand == 0) {
+        f[row] = st.j1;
+        alpha[row] = st.d1 * inv[st.j1];
+    } else {
+        int* e = q_entries + atomicAdd(q_count, 1) * kRedoInts;
+        e[0] = row; e[1] = ncand; e[2] = st.j1; e[3] = c1; e[4] = c2; e[5] = c3;
+    }
+}
+
+// Called by the whole workgroup (NWAVES waves) after a barrier that follows the last decide_or_queue.
+template <typename TR, int NWAVES>
+__device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
+                                            const double* __restrict__ cn2, int nch, int k, int32_t* __restrict__ f,
+                                            float* __restrict__ alpha, const int* q_count, const int* q_entries) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int total = *q_count;
+    for (int t = wave; t < total; t += NWAVES) {
+        const int* e = q_entries + t * kRedoInts;
+        const int row = e[0], rn = e[1];
+        const u32x4_t* xr = X + size_t(row) * nch;
         double bs = -1.0, bd = 0.0, bc = 1.0;
         int bj = 0;
-        auto eval = [&](int j) {
-            double d = wave_dot<TR>(xr, C + size_t(j) * nch, nch, lane);
-            double c2n = cn2[j];
-            double sc = c2n > 0.0 ? d * d / c2n : 0.0;
-            if (sc > bs) { bs = sc; bd = d; bc = c2n; bj = j; }       // strict: lowest j keeps a tie
+        auto take = [&](int j, double d) {
+            const double c2n = cn2[j];
+            const double sc = c2n > 0.0 ? d * d / c2n : 0.0;
+            if (sc > bs) { bs = sc; bd = d; bc = c2n; bj = j; }                   // strict: lowest j keeps a tie
+        };
+        auto eval2 = [&](int ja, int jb) {                     // ja <= jb; ja == jb evaluates one generator
+            double da, db;
+            wave_dot2<TR>(xr, C + size_t(ja) * nch, C + size_t(jb) * nch, nch, da, db);
+            take(ja, da);
+            if (jb != ja) take(jb, db);
         };
         if (rn < 4) {
-            const int cnt = rn + 1;
-            // candidates in increasing j (all values are wave-uniform)
-            for (int a = 1; a < cnt; ++a)
-                for (int q = a; q > 0 && cj[q] < cj[q - 1]; --q) { int t = cj[q]; cj[q] = cj[q - 1]; cj[q - 1] = t; }
-            for (int a = 0; a < cnt; ++a) eval(cj[a]);
+            // the named candidates in increasing j; unused slots sort to the end
+            constexpr int kNone = 0x7fffffff;
+            int a0 = e[2], a1 = e[3], a2 = rn >= 2 ? e[4] : kNone, a3 = rn >= 3 ? e[5] : kNone;
+            auto cx = [](int& x, int& y) { const int lo = min(x, y), hi = max(x, y); x = lo; y = hi; };
+            cx(a0, a1); cx(a2, a3); cx(a0, a2); cx(a1, a3); cx(a1, a2);
+            eval2(a0, a1);
+            if (rn == 2) eval2(a2, a2);
+            if (rn == 3) eval2(a2, a3);
         } else {
-            for (int j = 0; j < k; ++j) eval(j);
+#pragma unroll 1
+            for (int j0 = 0; j0 < k; j0 += 2) eval2(j0, min(j0 + 1, k - 1));
         }
-        if (lane == L) {
-            fi = bj;
-            al = bc > 0.0 ? float(bd / bc) : 0.f;
+        if (lane == 0) {
+            f[row] = bj;
+            alpha[row] = bc > 0.0 ? float(bd / bc) : 0.f;
         }
     }
 }
@@ -231,6 +262,8 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 
     __shared__ u32x4_t lds_raw[2 * CBUF + NW * 2 * XSLOT];
     __shared__ __attribute__((aligned(16))) float lds_inv[GB];
+    __shared__ int redo_count;
+    __shared__ int redo_entries[FUSED ? 32 * TT * NW * kRedoInts : 1];   // every token of the tile could need a second look
     u32x4_t* const lds_c = lds_raw;                                         // [2][CBUF]
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
@@ -239,6 +272,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     const int rt = blockIdx.x / ncb;
     const int gen0 = cb * GB;
 
+    if (tid == 0) redo_count = 0;                  // published by the barriers of the main loop
     for (int t = tid; t < GB; t += NT) {
         const int j = gen0 + t;
         lds_inv[t] = j < k ? inv[j] : -1.f;        // negative marks a slot past the last generator
@@ -480,16 +514,14 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
             }
         }
         if (FUSED) {
-            int fi;
-            float al;
-            decide_rows<TR>(X, C, inv, cn2, hash, nch, k, g == 0 && row < b, row, best, fi, al);
-            if (g == 0 && row < b) {
-                f[row] = fi;
-                alpha[row] = al;
-            }
+            decide_or_queue<TR>(inv, cn2, hash, g == 0 && row < b, row, best, f, alpha, &redo_count, redo_entries);
         } else {
             if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
         }
+    }
+    if (FUSED) {
+        __syncthreads();
+        drain_queue<TR, NW>(X, C, cn2, nch, k, f, alpha, &redo_count, redo_entries);
     }
 }
 
@@ -512,13 +544,13 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
             if (cb == 0) st = o; else st.merge(o);
         }
     }
-    int fi;
-    float al;
-    decide_rows<TR>(X, C, inv, cn2, hash, nch, k, valid, row, st, fi, al);
-    if (valid) {
-        f[row] = fi;
-        alpha[row] = al;
-    }
+    __shared__ int redo_count;
+    __shared__ int redo_entries[256 * kRedoInts];
+    if (threadIdx.x == 0) redo_count = 0;
+    __syncthreads();
+    decide_or_queue<TR>(inv, cn2, hash, valid, row, st, f, alpha, &redo_count, redo_entries);
+    __syncthreads();
+    drain_queue<TR, 4>(X, C, cn2, nch, k, f, alpha, &redo_count, redo_entries);
 }
 
 // ------------------------------------------------------------------------------------------------ host side
