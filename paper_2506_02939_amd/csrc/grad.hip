@@ -223,33 +223,43 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int slice = blockIdx.x;
 
-    for (int q = tid; q < 18 * k; q += 1024) wh[q] = 0;      // wh, tot and bef are contiguous
-    __syncthreads();
+    // every global load of the kernel is issued up front (keys, weights, this thread's share of the table), so the
+    // kernel pays one memory latency, not one per phase
     int key[4];
     const int i0 = slice * kSliceRows + 4 * tid;      // wave w owns rows [256 w, 256 w + 256) of the slice
     load_keys(f, i0, b, k, key);
+    float al[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) al[c] = alpha[min(i0 + c, b - 1)];
+    // rows of every generator in earlier slices / in all slices: column sums of the table, taken in parallel by all
+    // threads (each sums a strip of slices for one generator, two generators per thread when k > 1024)
+    const int strips = k <= 1024 ? 1024 / max(k, 1) : 1;            // threads per generator (power-of-two k: exact)
+    int before[2] = {0, 0}, total[2] = {0, 0};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int j = h * 1024 + (strips > 1 ? tid % k : tid);
+        const int strip = strips > 1 ? tid / k : 0;
+        if (j < k && strip < strips && (h == 0 || k > 1024)) {
+            for (int s = strip; s < nslices; s += strips) {
+                const int c = table[size_t(s) * k + j];
+                before[h] += s < slice ? c : 0;
+                total[h] += c;
+            }
+        }
+    }
+
+    for (int q = tid; q < 18 * k; q += 1024) wh[q] = 0;      // wh, tot and bef are contiguous
+    __syncthreads();
 #pragma unroll
     for (int c = 0; c < 4; ++c)
         if (key[c] < k) atomicAdd(&wh[wave * k + key[c]], 1);
-    __syncthreads();
-
-    // rows of every generator in earlier slices / in all slices: column sums of the table, taken in parallel by all
-    // threads (each sums a strip of slices for one generator), then folded through LDS
-    {
-        const int strips = k <= 1024 ? 1024 / max(k, 1) : 1;        // threads per generator (power-of-two k: exact)
-        for (int j0 = 0; j0 < k; j0 += 1024) {
-            const int j = j0 + (strips > 1 ? tid % k : tid);
-            const int strip = strips > 1 ? tid / k : 0;
-            int before = 0, total = 0;
-            if (j < k && strip < strips) {
-                for (int s = strip; s < nslices; s += strips) {
-                    const int c = table[size_t(s) * k + j];
-                    before += s < slice ? c : 0;
-                    total += c;
-                }
-                atomicAdd(&tot[j], total);           // tot and bef start at zero (cleared with wh below)
-                atomicAdd(&bef[j], before);
-            }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int j = h * 1024 + (strips > 1 ? tid % k : tid);
+        const int strip = strips > 1 ? tid / k : 0;
+        if (j < k && strip < strips && (h == 0 || k > 1024)) {
+            atomicAdd(&tot[j], total[h]);
+            atomicAdd(&bef[j], before[h]);
         }
     }
     __syncthreads();
@@ -302,7 +312,7 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
         if (key[c] < k) {
             const int pos = tot[key[c]] + atomicAdd(&wh[wave * k + key[c]], 1);
             perm[pos] = i0 + c;
-            alpha_s[pos] = alpha[i0 + c];
+            alpha_s[pos] = al[c];
             key_s[pos] = key[c];
         }
     }
@@ -317,7 +327,9 @@ template <typename TR> struct RowLoad;
 template <> struct RowLoad<Bf16> {      // 8 columns = one 16-byte chunk
     u32x4_t v;
     static constexpr int kGroup = 8;     // rows fetched per group
-    __device__ __forceinline__ void load(const u32x4_t* __restrict__ rowp, int ch, int) { v = rowp[ch]; }
+    // dY is read exactly once: non-temporal loads keep the stream from evicting what is reused (the sorted lists,
+    // the partial rows, X and C of the next compression) from L2 and the Infinity Cache
+    __device__ __forceinline__ void load(const u32x4_t* __restrict__ rowp, int ch, int) { v = __builtin_nontemporal_load(&rowp[ch]); }
     __device__ __forceinline__ void fma(float a, float (&acc)[8]) const {
         float e[8];
         Bf16::unpack(v, e);
@@ -331,7 +343,10 @@ template <> struct RowLoad<Bf16> {      // 8 columns = one 16-byte chunk
 template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
     u32x4_t v0, v1;
     static constexpr int kGroup = 4;
-    __device__ __forceinline__ void load(const u32x4_t* __restrict__ rowp, int ch, int mch) { v0 = rowp[ch]; v1 = rowp[min(ch + 1, mch - 1)]; }
+    __device__ __forceinline__ void load(const u32x4_t* __restrict__ rowp, int ch, int mch) {
+        v0 = __builtin_nontemporal_load(&rowp[ch]);
+        v1 = __builtin_nontemporal_load(&rowp[min(ch + 1, mch - 1)]);
+    }
     __device__ __forceinline__ void fma(float a, float (&acc)[8]) const {
         acc[0] = fmaf(a, __uint_as_float(v0.x), acc[0]); acc[1] = fmaf(a, __uint_as_float(v0.y), acc[1]);
         acc[2] = fmaf(a, __uint_as_float(v0.z), acc[2]); acc[3] = fmaf(a, __uint_as_float(v0.w), acc[3]);
@@ -343,9 +358,6 @@ template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
 
 // Workgroup = 4 waves that share a chunk of the list and sit side by side along the row: wave w covers W
 // consecutive 512-column groups, so the workgroup reads 4*W KiB of every row at (nearly) the same time.
-#if defined(PAMM_DBG_TIME)
-__device__ unsigned long long g_dbg_ctime[2 * 4096];
-#endif
 template <typename TR, int W>
 __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const int32_t* __restrict__ perm,
                                                   const float* __restrict__ alpha_s, const int32_t* __restrict__ key_s, int b,
@@ -354,9 +366,6 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp0 = (wc * 4 + wave) * W;
     if (grp0 * 512 >= m) return;                           // this wave has no columns (uniform per wave)
-#if defined(PAMM_DBG_TIME)
-    if (threadIdx.x == 0 && blockIdx.x < 4096) g_dbg_ctime[blockIdx.x * 2] = wall_clock64();
-#endif
     const int s0 = chunk * P;
     const int s1 = min(b, s0 + P);
     int ch[W];
@@ -446,9 +455,6 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
         rows_of(rb, s + 5 * U);
     }
     flush(cur);
-#if defined(PAMM_DBG_TIME)
-    if (threadIdx.x == 0 && blockIdx.x < 4096) g_dbg_ctime[blockIdx.x * 2 + 1] = wall_clock64();
-#endif
 }
 
 // Btilde_j = sum of generator j's partial rows (only used by pamm_contract).
@@ -618,7 +624,9 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
     }
 
     // D layout of the 32x32 MFMA: register i of lane (r,g) is row 8*(i/4)+4*g+(i%4), column r: one store
-    // instruction writes two full 128-byte row segments.
+    // instruction writes two full 128-byte row segments.  The stores are non-temporal: dW is not read again by this
+    // library, and as ordinary stores its dirty lines are written back later, in the middle of the next kernels'
+    // streams (measured: 25 % slower k_contract and k_score at the 7B-shaped layer).
     const int lw = l0 + wy * 64, cw = c0 + wx * 64;
 #pragma unroll
     for (int fa = 0; fa < 2; ++fa)
@@ -628,7 +636,7 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
-                if (l < n && c < m) dW[size_t(l) * m + c] = acc[fa][fb][i];
+                if (l < n && c < m) __builtin_nontemporal_store(acc[fa][fb][i], &dW[size_t(l) * m + c]);
             }
         }
 }
@@ -763,9 +771,3 @@ extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* a
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
-
-#if defined(PAMM_DBG_TIME)
-extern "C" int pamm_dbg_read_ctime(unsigned long long* out_host, int count) {
-    return int(hipMemcpyFromSymbol(out_host, HIP_SYMBOL(pamm::g_dbg_ctime), sizeof(unsigned long long) * count));
-}
-#endif
