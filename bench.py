@@ -2,7 +2,8 @@
 """Benchmark of the PAMM hot path on one MI355X: one step = pamm_compress + pamm_grad over one synthetic batch.
 
 Prints ONE JSON line.  `value` is tokens/s = b / (t_compress + t_grad) with X and dY resident in HBM before the
-timed region.  `roofline` covers the dominant kernel (k_contract, the single pass over dY): algorithmic bytes per
+timed region; consecutive steps rotate through `--sets` copies of the inputs so that a step finds none of its
+inputs in the Infinity Cache.  `roofline` covers the dominant kernel (k_contract, the single pass over dY): algorithmic bytes per
 launch divided by its mean duration, the latter measured here with HIP events on the launch stream (the library's
 own per-kernel event hooks) over a second run of the same K steps.  `cpu_baseline` is the fp64 oracle timed on
 this machine's host cores on the same batch.  `exact_gemm` is the plain X^T dY product (vendor BLAS through
@@ -52,6 +53,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama1b")
+    ap.add_argument("--sets", type=int, default=2,
+                    help="copies of (X, dY) in HBM that consecutive steps rotate through, so that no input survives in the "
+                         "256 MiB Infinity Cache from one step to the next (1 = every step re-reads the same buffers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -70,7 +74,10 @@ def main() -> int:
 
     w = workloads.WORKLOADS[args.workload]
     X_cpu, dY_cpu = workloads.generate(w)
-    X, dY = X_cpu.cuda(), dY_cpu.cuda()
+    nsets = max(1, args.sets)
+    Xs = [X_cpu.cuda() for _ in range(nsets)]
+    dYs = [dY_cpu.cuda() for _ in range(nsets)]
+    X, dY = Xs[0], dYs[0]
     b, n, m, k = w.b, w.n, w.m, w.k
     dt = pamm.PAMM_BF16 if w.dtype == "bf16" else pamm.PAMM_F32
 
@@ -81,8 +88,8 @@ def main() -> int:
     ws_g = torch.empty(pamm.grad_workspace(b, n, k, m, dt), dtype=torch.uint8, device="cuda")
 
     def step(i):
-        pamm.compress(X, k, seed=i, out=out, ws=ws_c)          # fresh generators every step, as in training (App. F)
-        pamm.grad(out.C, out.f, out.alpha, dY, out=dW, ws=ws_g)
+        pamm.compress(Xs[i % nsets], k, seed=i, out=out, ws=ws_c)      # fresh generators every step, as in training (App. F)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], out=dW, ws=ws_g)
 
     for i in range(args.warmup):
         step(i)
@@ -100,9 +107,9 @@ def main() -> int:
     reps = max(1, min(args.steps, 50))
     for i in range(reps):
         ev[0].record()
-        pamm.compress(X, k, seed=i, out=out, ws=ws_c)
+        pamm.compress(Xs[i % nsets], k, seed=i, out=out, ws=ws_c)
         ev[1].record()
-        pamm.grad(out.C, out.f, out.alpha, dY, out=dW, ws=ws_g)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], out=dW, ws=ws_g)
         ev[2].record()
         torch.cuda.synchronize()
         tc += ev[0].elapsed_time(ev[1])
@@ -144,7 +151,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "b": b, "n": n, "m": m, "k": k, "dtype": w.dtype,
-                   "recipe": f"{w.centres} centres, sigma {w.sigma}, {w.structure}, pad {w.pad_frac}"},
+                   "recipe": f"{w.centres} centres, sigma {w.sigma}, {w.structure}, pad {w.pad_frac}",
+                   "input_sets_rotated": nsets},
         "ms_compress": round(tc, 4), "ms_grad": round(tg, 4),
         "roofline": roofline,
         "kernels": kernels,
@@ -177,14 +185,20 @@ def main() -> int:
         from oracle import pamm_oracle
 
         pamm_oracle.build()
-        c0 = time.perf_counter()
-        oc = pamm_oracle.compress(X_cpu, k, seed=0)
-        c1 = time.perf_counter()
-        pamm_oracle.grad(oc.C, oc.f, oc.alpha, dY_cpu)
-        c2 = time.perf_counter()
+        best = None
+        reps_cpu = 3
+        for _ in range(reps_cpu):
+            c0 = time.perf_counter()
+            oc = pamm_oracle.compress(X_cpu, k, seed=0)
+            c1 = time.perf_counter()
+            pamm_oracle.grad(oc.C, oc.f, oc.alpha, dY_cpu)
+            c2 = time.perf_counter()
+            if best is None or c2 - c0 < best[0]:
+                best = (c2 - c0, c1 - c0, c2 - c1)
         result["cpu_baseline"] = {
-            "value": round(b / (c2 - c0), 1), "unit": "tokens/s", "cores": pamm_oracle.threads(), "kind": "oracle",
-            "sample": f"the full {w.name} batch ({b} tokens), one repetition: compress {c1 - c0:.2f} s + grad {c2 - c1:.2f} s",
+            "value": round(b / best[0], 1), "unit": "tokens/s", "cores": pamm_oracle.threads(), "kind": "oracle",
+            "sample": f"the full {w.name} batch ({b} tokens), best of {reps_cpu} repetitions: "
+                      f"compress {best[1]:.2f} s + grad {best[2]:.2f} s",
         }
 
     print(json.dumps(result), flush=True)
