@@ -19,33 +19,25 @@
 namespace pamm {
 
 // ------------------------------------------------------------------------------------------------
-// Per-token running record of the best generators seen so far.  Equal scores are not listed twice:
-// s1 > s2 > s3 > s4 are the four largest DISTINCT score values; j1 / j2 / j3 are the lowest generator
-// numbers attaining s1 / s2 / s3; jt is the lowest generator other than j1 that attains s1 exactly
-// (-1 if none).  Bit-identical generators (padding tokens sampled twice) produce bit-identical scores,
-// so they meet in jt instead of hiding the real runners-up.
+// Per-token record of the leading scores.  s1 > s2 > s3 > s4 are the four largest DISTINCT score values known;
+// j1 / j2 / j3 are the lowest generator numbers attaining s1 / s2 / s3 (j3 = -1: the third value is known but not
+// who attains it; s4 is a value only); d1 is the dot product behind s1; jt is the lowest generator other than j1
+// that attains s1 exactly (-1 if none).  Bit-identical generators (padding tokens sampled twice) produce
+// bit-identical scores, so they meet in jt instead of hiding the real runners-up.
 struct Best {
     float s1; int j1; float d1; int jt; float s2; int j2; float s3; int j3; float s4;
 
     __device__ __forceinline__ void init() {
-        s1 = -1.f; j1 = 0; d1 = 0.f; jt = -1; s2 = -2.f; j2 = 0; s3 = -3.f; j3 = 0; s4 = -4.f;
+        s1 = -1.f; j1 = 0; d1 = 0.f; jt = -1; s2 = -2.f; j2 = 0; s3 = -3.f; j3 = -1; s4 = -4.f;
     }
 
-    // generators arrive in increasing j
-    __device__ __forceinline__ void push(float s, int j, float d) {
-        if (s > s1) { s4 = s3; s3 = s2; j3 = j2; s2 = s1; j2 = j1; s1 = s; j1 = j; d1 = d; jt = -1; }
-        else if (s == s1) { if (jt < 0) jt = j; }
-        else if (s > s2) { s4 = s3; s3 = s2; j3 = j2; s2 = s; j2 = j; }
-        else if (s == s2) { }
-        else if (s > s3) { s4 = s3; s3 = s; j3 = j; }
-        else if (s < s3 && s > s4) { s4 = s; }
-    }
-
-    __device__ __forceinline__ void insert_lower(float s, int j) {   // s < s1
+    // A value below s1; j = -1 if it is not known who attains it.  Such a value never ranks second: in the record it
+    // comes from, two larger values stand above it.
+    __device__ __forceinline__ void insert_lower(float s, int j) {
         if (s > s2) { s4 = s3; s3 = s2; j3 = j2; s2 = s; j2 = j; }
-        else if (s == s2) { j2 = min(j2, j); }
+        else if (s == s2) { if (j >= 0) j2 = min(j2, j); }
         else if (s > s3) { s4 = s3; s3 = s; j3 = j; }
-        else if (s == s3) { j3 = min(j3, j); }
+        else if (s == s3) { j3 = (j3 < 0 || j < 0) ? max(j3, j) : min(j3, j); }
         else if (s > s4) { s4 = s; }
     }
 
@@ -78,7 +70,7 @@ struct Best {
         s1 = __uint_as_float(p.x); d1 = __uint_as_float(p.y); s2 = __uint_as_float(p.z); s3 = __uint_as_float(p.w);
         s4 = __uint_as_float(q.x);
         j1 = int(q.y & 0xffffu); jt = int(q.y >> 16); jt = jt == 0xffff ? -1 : jt;
-        j2 = int(q.z & 0xffffu); j3 = int(q.z >> 16);
+        j2 = int(q.z & 0xffffu); j3 = int(q.z >> 16); j3 = j3 == 0xffff ? -1 : j3;
     }
 };
 
@@ -127,28 +119,42 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
 
 // ------------------------------------------------------------------------------------------------
 // The final word on f(i) and alpha_i.  A token whose leading scores are within 2^-12 (relative) of each other is
-// re-decided in fp64: among up to four named candidates when at most three distinct values are that close, among
-// all generators otherwise.  Such tokens are rare but unevenly spread, so a workgroup pools them in an LDS queue
-// (decide_or_queue, called by every lane for its token) and its waves then share them out (drain_queue, called by
-// the whole workgroup); one wave re-decides one token at a time, with the rows of all candidates in flight at once.
-constexpr int kRedoInts = 6;     // row, ncand, j1, c1, c2, c3
+// re-decided in fp64: among up to four named candidates (the winner, a non-identical generator that ties with it
+// exactly, the runners-up) when every value that close has a name, among all generators otherwise (in the
+// workloads here: never seen; three values that close: one token in 250 000).  Such tokens are rare but unevenly
+// spread, so a workgroup pools them in an LDS queue (decide_or_queue, called by every lane for its token) and its
+// waves then share them out (drain_queue, called by the whole workgroup).
+constexpr int kRedoInts = 6;     // row, number of extra candidates (4 = all generators), j1, c1, c2, c3
 
-// dot products of one row of X with two generators, in fp64, by the whole wave.  This code runs a handful of times
-// per launch: it is kept small (rolled loops) because every instruction of it is an instruction-cache miss.
+// Dot products of one row of X with two generators, in fp64, by the whole wave.  This code runs a handful of times
+// per launch, on the critical path of its workgroup: loads go out four chunks per lane at a time (one memory
+// latency for rows of up to 256 chunks), and the code is kept small because all of it misses the instruction cache.
 template <typename TR>
 __device__ __noinline__ void wave_dot2(const u32x4_t* __restrict__ x, const u32x4_t* __restrict__ ca, const u32x4_t* __restrict__ cb,
                                        int nch, double& da, double& db) {
     double acc0 = 0.0, acc1 = 0.0;
+    const int lane = threadIdx.x & 63;
 #pragma unroll 1
-    for (int q = threadIdx.x & 63; q < nch; q += kWave) {
-        float a[TR::kPerChunk], b0[TR::kPerChunk], b1[TR::kPerChunk];
-        TR::unpack(x[q], a);
-        TR::unpack(ca[q], b0);
-        TR::unpack(cb[q], b1);
+    for (int q0 = 0; q0 < nch; q0 += 4 * kWave) {
+        u32x4_t xv[4], av[4], bv[4];
 #pragma unroll
-        for (int e = 0; e < TR::kPerChunk; ++e) {
-            acc0 += double(a[e]) * double(b0[e]);
-            acc1 += double(a[e]) * double(b1[e]);
+        for (int t = 0; t < 4; ++t) {
+            const int q = q0 + t * kWave + lane;
+            const uint32_t keep = q < nch ? 0xffffffffu : 0u;       // chunks past the end of the row count as zeros
+            const int qq = min(q, nch - 1);
+            xv[t] = x[qq] & keep; av[t] = ca[qq]; bv[t] = cb[qq];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float a[TR::kPerChunk], b0[TR::kPerChunk], b1[TR::kPerChunk];
+            TR::unpack(xv[t], a);
+            TR::unpack(av[t], b0);
+            TR::unpack(bv[t], b1);
+#pragma unroll
+            for (int e = 0; e < TR::kPerChunk; ++e) {
+                acc0 += double(a[e]) * double(b0[e]);
+                acc1 += double(a[e]) * double(b1[e]);
+            }
         }
     }
     da = wave_sum(acc0);
@@ -156,22 +162,24 @@ __device__ __noinline__ void wave_dot2(const u32x4_t* __restrict__ x, const u32x
 }
 
 // Called by every lane.  Writes f and alpha of the lane's token unless it needs a second look; then it is queued.
-template <typename TR>
 __device__ __forceinline__ void decide_or_queue(const float* __restrict__ inv, const double* __restrict__ cn2,
                                                 const unsigned long long* __restrict__ hash, bool valid, int row, const Best& st,
                                                 int32_t* __restrict__ f, float* __restrict__ alpha, int* q_count, int* q_entries) {
-    int ncand = 0, c1 = 0, c2 = 0, c3 = 0;     // extra candidates beside j1 (ncand = 4 means "all generators")
-    if (valid && st.s1 > 0.f) {
+    if (!valid) return;
+    int ncand = 0, c1 = 0, c2 = 0, c3 = 0;
+    if (st.s1 > 0.f) {
         const float thr = st.s1 * (1.f - 0x1p-12f);
         // an exact tie between two generators whose rows are bit-identical needs no second look: the lower one wins
         if (st.jt >= 0 &&
             !(hash[st.j1] == hash[st.jt] && __double_as_longlong(cn2[st.j1]) == __double_as_longlong(cn2[st.jt])))
             c1 = st.jt, ncand = 1;
         if (st.s2 >= thr) { (ncand == 0 ? c1 : c2) = st.j2; ++ncand; }
-        if (st.s3 >= thr) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
+        if (st.s3 >= thr) {
+            if (st.j3 >= 0) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
+            else ncand = 4;
+        }
         if (st.s4 >= thr) ncand = 4;
     }
-    if (!valid) return;
     if (ncand == 0) {
         f[row] = st.j1;
         alpha[row] = st.d1 * inv[st.j1];
@@ -194,16 +202,16 @@ __device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const
         const u32x4_t* xr = X + size_t(row) * nch;
         double bs = -1.0, bd = 0.0, bc = 1.0;
         int bj = 0;
-        auto take = [&](int j, double d) {
-            const double c2n = cn2[j];
+        auto take = [&](int j, double d, double c2n) {
             const double sc = c2n > 0.0 ? d * d / c2n : 0.0;
             if (sc > bs) { bs = sc; bd = d; bc = c2n; bj = j; }                   // strict: lowest j keeps a tie
         };
         auto eval2 = [&](int ja, int jb) {                     // ja <= jb; ja == jb evaluates one generator
+            const double na = cn2[ja], nb = cn2[jb];          // in flight together with the rows
             double da, db;
             wave_dot2<TR>(xr, C + size_t(ja) * nch, C + size_t(jb) * nch, nch, da, db);
-            take(ja, da);
-            if (jb != ja) take(jb, db);
+            take(ja, da, na);
+            if (jb != ja) take(jb, db, nb);
         };
         if (rn < 4) {
             // the named candidates in increasing j; unused slots sort to the end
@@ -412,7 +420,6 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     constexpr int SROW = PG + 4;             // floats per token row (padding: conflict-free 16-byte accesses)
     static_assert(NW * 32 * SROW * sizeof(float) <= sizeof(lds_raw), "score dump does not fit");
     float* sdump = reinterpret_cast<float*>(lds_raw) + wave * (32 * SROW);
-    const float kClose = 1.f - 0x1p-12f;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         auto dump = [&](int h) {                 // scores of pass h -> this wave's LDS tile, [token][generator]
@@ -428,10 +435,11 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         };
         const float* srow = &sdump[r * SROW + g * (PG / 2)];
 
-        // Round 1 (always): per lane, over its half of every pass: the largest score m1 (lowest j on ties), the
-        // lowest other generator reaching it exactly (jt), and the largest score strictly below it (m2).
-        float m1 = -1.f, m2 = -2.f, dm = 0.f;
-        int jm = 0, jt = -1;
+        // Per lane, over its half of every pass: the largest score m1 (lowest j on ties) with its dot product, the
+        // lowest other generator reaching m1 exactly (jt), the largest score strictly below m1 (m2, lowest j: j2)
+        // and the largest strictly below m2 (m3, value only).
+        float m1 = -1.f, m2 = -2.f, m3 = -3.f, dm = 0.f;
+        int jm = 0, jt = -1, j2 = 0;
 #pragma unroll
         for (int h = 0; h < TG / PF; ++h) {
             dump(h);
@@ -446,7 +454,11 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                     const float sc = iv[e] >= 0.f ? dd[e] * dd[e] * iv[e] : -3.f;      // slots past the last generator
                     const int j = gen0 + jl0 + c + e;
                     const bool up = sc > m1, tie = sc == m1;
-                    m2 = up ? m1 : ((!tie && sc > m2) ? sc : m2);
+                    const bool mid = !up && !tie && sc > m2;
+                    const bool low = sc < m2 && sc > m3;
+                    m3 = (up || mid) ? m2 : (low ? sc : m3);
+                    j2 = up ? jm : (mid ? j : j2);
+                    m2 = up ? m1 : (mid ? sc : m2);
                     jt = up ? -1 : ((tie && jt < 0) ? j : jt);
                     dm = up ? dd[e] : dm;
                     jm = up ? j : jm;
@@ -455,35 +467,16 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
             }
             wave_lds_sync();
         }
-        // the two lanes of a token join their halves
-        {
-            const float o1 = __shfl_xor(m1, 32), o2 = __shfl_xor(m2, 32), od = __shfl_xor(dm, 32);
-            const int oj = __shfl_xor(jm, 32), ot = __shfl_xor(jt, 32);
-            if (o1 > m1) {
-                m2 = fmaxf(fmaxf(m1, m2), o2);
-                m1 = o1; jm = oj; dm = od; jt = ot;
-            } else if (o1 == m1) {
-                int t = max(jm, oj);
-                if (jt >= 0) t = min(t, jt);
-                if (ot >= 0) t = min(t, ot);
-                if (oj < jm) dm = od;
-                jm = min(jm, oj); jt = t;
-                m2 = fmaxf(m2, o2);
-            } else {
-                m2 = fmaxf(fmaxf(o1, o2), m2);
-            }
-        }
-        const bool close = m1 > 0.f && m2 >= m1 * kClose;
-        const int row = row_base + 32 * tt + r;
         Best best;
         best.init();
-        best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt;
-        // If nobody in this wave has a distinct runner-up within 2^-12, the record is the winner (and its exact ties).
-        if (__builtin_amdgcn_ballot_w64(close) != 0ull) {
-            // Round 2 (few waves): now that the winner is known, list the distinct scores within 2^-12 of it.
-            // Only those can matter to the final decision, and they are rare, so the scan is one compare per
-            // generator with an insertion when a lane finds one.
-            const float thr = m1 * kClose;
+        best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt; best.s2 = m2; best.j2 = j2; best.s3 = m3;
+        // Second pass, in the rare wave where some lane has three distinct values within 2^-12 of each other: list who
+        // attains the values that close to the lane's maximum (only those can matter to the final decision).
+        const bool crowded = m1 > 0.f && m3 >= m1 * (1.f - 0x1p-12f);
+        if (__builtin_amdgcn_ballot_w64(crowded) != 0ull) {
+            const float thr = m1 * (1.f - 0x1p-12f);
+            best.s2 = -2.f; best.j2 = 0; best.s3 = -3.f; best.j3 = -1; best.s4 = -4.f;
+            if (!crowded) { best.s2 = m2; best.j2 = j2; best.s3 = m3; }
 #pragma unroll
             for (int h = 0; h < TG / PF; ++h) {
                 dump(h);
@@ -496,7 +489,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float sc = iv[e] >= 0.f ? dd[e] * dd[e] * iv[e] : -3.f;
-                        const bool hit = close && sc >= thr && sc < m1;
+                        const bool hit = crowded && sc >= thr && sc < m1;
                         if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
                             if (hit) best.insert_lower(sc, gen0 + jl0 + c + e);
                         }
@@ -504,17 +497,18 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 }
                 wave_lds_sync();
             }
-            // join the two halves of the token: both lanes hold the same winner, only the close values differ
-            {
-                const float o2 = __shfl_xor(best.s2, 32), o3 = __shfl_xor(best.s3, 32), o4 = __shfl_xor(best.s4, 32);
-                const int p2 = __shfl_xor(best.j2, 32), p3 = __shfl_xor(best.j3, 32);
-                best.insert_lower(o2, p2);
-                best.insert_lower(o3, p3);
-                if (o4 < best.s3 && o4 > best.s4) best.s4 = o4;
-            }
         }
+        // the two lanes of a token join their halves
+        {
+            Best o;
+            o.s1 = __shfl_xor(best.s1, 32); o.j1 = __shfl_xor(best.j1, 32); o.d1 = __shfl_xor(best.d1, 32);
+            o.jt = __shfl_xor(best.jt, 32); o.s2 = __shfl_xor(best.s2, 32); o.j2 = __shfl_xor(best.j2, 32);
+            o.s3 = __shfl_xor(best.s3, 32); o.j3 = __shfl_xor(best.j3, 32); o.s4 = __shfl_xor(best.s4, 32);
+            best.merge(o);
+        }
+        const int row = row_base + 32 * tt + r;
         if (FUSED) {
-            decide_or_queue<TR>(inv, cn2, hash, g == 0 && row < b, row, best, f, alpha, &redo_count, redo_entries);
+            decide_or_queue(inv, cn2, hash, g == 0 && row < b, row, best, f, alpha, &redo_count, redo_entries);
         } else {
             if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
         }
@@ -548,7 +542,7 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
     __shared__ int redo_entries[256 * kRedoInts];
     if (threadIdx.x == 0) redo_count = 0;
     __syncthreads();
-    decide_or_queue<TR>(inv, cn2, hash, valid, row, st, f, alpha, &redo_count, redo_entries);
+    decide_or_queue(inv, cn2, hash, valid, row, st, f, alpha, &redo_count, redo_entries);
     __syncthreads();
     drain_queue<TR, 4>(X, C, cn2, nch, k, f, alpha, &redo_count, redo_entries);
 }
