@@ -125,6 +125,8 @@ SMALL = [
     ("bf16_many_rows", "llama60m", dict(seqs=7, seq_len=10001, n=16, m=24, k=3, centres=6)),   # b > 65536: streaming grouping path
     ("f32_k17_pad16", "tiny", dict(seqs=2, seq_len=97, n=44, m=36, k=17, centres=20)),
     ("bf16_k2500_per_generator_grouping", "llama1b", dict(seqs=3, seq_len=1000, n=32, m=40, k=2500, centres=3000)),
+    # b > 65536 together with k > 2048: the grouping kernel that streams f twice
+    ("bf16_many_rows_many_generators", "llama1b", dict(seqs=6, seq_len=11003, n=8, m=8, k=2100, centres=2500)),
 ]
 
 
@@ -194,6 +196,35 @@ def test_near_ties_are_decided_like_fp64(pamm, oracle):
     ora, got = run_case(pamm, oracle, X, dY, k, "f32", idx=list(range(k)), label="near ties f32")
     gap = (ora.best - ora.second) / ora.best
     assert (gap < 1e-4).sum() > 100           # the case really exercises the fp64 re-decision
+    sel = gap >= 1e-6
+    assert np.array_equal(got.f.cpu().numpy()[sel], ora.f[sel])
+
+
+@pytest.mark.parametrize("k,slots", [(8, [0, 1, 2, 3, 4, 5]), (300, [3, 40, 130, 258, 259, 299])],
+                         ids=["one_column_block", "two_column_blocks"])
+def test_crowded_near_ties(pamm, oracle, k, slots):
+    """Rows that sit (almost) equally close to 3, 4, 5 or 6 generators at once, with score gaps of 1e-5 .. 1e-7:
+    three or four values that close go through the naming pass, five or six through the all-generators second look.
+    Whatever the path, f must be the fp64 decision down to the 1e-6 bar."""
+    g = torch.Generator().manual_seed(11)
+    n = 384
+    G = torch.randn(k, n, generator=g, dtype=torch.float64)
+    # the generators the rows crowd around are orthonormal, so a plain sum of them scores equally on each
+    Q, _ = torch.linalg.qr(G[slots].T)
+    G[slots] = Q.T
+    rows = [G[j].clone() for j in range(k)]
+    crowd = []
+    for rep in range(240):
+        m = 3 + rep % 4
+        pick = [slots[i] for i in torch.randperm(len(slots), generator=g)[:m].tolist()]
+        w = 1.0 + (10.0 ** (-5 - 2 * torch.rand(m, generator=g, dtype=torch.float64))) * torch.randn(m, generator=g, dtype=torch.float64)
+        rows.append((w[:, None] * G[pick]).sum(0) * 3.0)
+        crowd.append(m)
+    X = torch.stack(rows).to(torch.float32)
+    dY = (0.1 * torch.randn(X.shape[0], 72, generator=g)).to(torch.float32)
+    ora, got = run_case(pamm, oracle, X, dY, k, "f32", idx=list(range(k)), label=f"crowded near ties k={k}")
+    gap = (ora.best - ora.second) / ora.best
+    assert (gap[k:] < 1e-4).mean() > 0.9          # the rows really are crowded
     sel = gap >= 1e-6
     assert np.array_equal(got.f.cpu().numpy()[sel], ora.f[sel])
 
