@@ -570,22 +570,26 @@ static void launch_score_cfg(const CompressPlan& pl, const ScoreArgs& a, hipStre
 
 template <typename TR, int TG, bool FUSED>
 static void launch_score_tg(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
-    if (pl.tt == 2) launch_score_cfg<TR, TG, 2, 4, FUSED>(pl, a, s);
-    else if (pl.nw == 8) launch_score_cfg<TR, TG, 1, 8, FUSED>(pl, a, s);
+    if (pl.nw == 8) launch_score_cfg<TR, TG, 1, 8, FUSED>(pl, a, s);
     else if (pl.nw == 4) launch_score_cfg<TR, TG, 1, 4, FUSED>(pl, a, s);
     else launch_score_cfg<TR, TG, 1, 2, FUSED>(pl, a, s);
 }
 
-// One column block (k <= 256): the fused kernel.  Several column blocks always use the widest block (TG = 8).
+// One column block: the fused kernel.  Several column blocks: one record per token and block for k_finalize.
+template <typename TR, bool FUSED>
+static void launch_score_blocks(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
+    switch (pl.tg) {
+        case 1: launch_score_tg<TR, 1, FUSED>(pl, a, s); break;
+        case 2: launch_score_tg<TR, 2, FUSED>(pl, a, s); break;
+        case 4: launch_score_tg<TR, 4, FUSED>(pl, a, s); break;
+        default: launch_score_tg<TR, 8, FUSED>(pl, a, s); break;
+    }
+}
+
 template <typename TR>
 static void launch_score(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
-    if (pl.ncb > 1) { launch_score_tg<TR, 8, false>(pl, a, s); return; }
-    switch (pl.tg) {
-        case 1: launch_score_tg<TR, 1, true>(pl, a, s); break;
-        case 2: launch_score_tg<TR, 2, true>(pl, a, s); break;
-        case 4: launch_score_tg<TR, 4, true>(pl, a, s); break;
-        default: launch_score_tg<TR, 8, true>(pl, a, s); break;
-    }
+    if (pl.ncb > 1) launch_score_blocks<TR, false>(pl, a, s);
+    else launch_score_blocks<TR, true>(pl, a, s);
 }
 
 template <typename TR>

@@ -20,8 +20,8 @@ inline int per_chunk(pamm_dtype dt) { return dt == PAMM_BF16 ? 8 : 4; }
 inline bool dtype_ok(pamm_dtype dt) { return dt == PAMM_F32 || dt == PAMM_BF16; }
 
 // Tuning overrides for experiments (read on every call; unset or invalid = use the built-in heuristic):
-//   PAMM_SCORE_TT    token fragments per wave in k_score (1 or 2)
-//   PAMM_SCORE_NW    waves per workgroup in k_score when PAMM_SCORE_TT is 1 (2, 4 or 8)
+//   PAMM_SCORE_TG    32-generator fragments per wave in k_score (1, 2, 4 or 8; at most what k allows)
+//   PAMM_SCORE_NW    waves per workgroup in k_score (2, 4 or 8)
 //   PAMM_PIECE_ROWS  list positions per chunk in k_contract (a multiple of 16, 16..4096)
 //   PAMM_CONTRACT_W  512-column groups per wave in k_contract (1..3)
 inline int env_int(const char* name) {
@@ -33,8 +33,8 @@ inline int env_int(const char* name) {
 
 struct CompressPlan {
     int tg;          // 32-generator fragments per wave (1, 2, 4 or 8): a column block holds 32*tg generators
-    int tt;          // 32-token fragments per wave (1 or 2)
-    int nw;          // waves per workgroup (2, 4 or 8; 4 when tt = 2): a workgroup holds 32*tt*nw tokens
+    int tt;          // 32-token fragments per wave (always 1: two were measured slower than twice the waves)
+    int nw;          // waves per workgroup (2, 4 or 8): a workgroup holds 32*tt*nw tokens
     int ncb;         // column blocks = ceil(k / (32*tg))
     int64_t row_tiles;
     // workspace offsets (bytes)
@@ -46,24 +46,31 @@ inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt,
     if (b < 1 || n < 1 || k < 1 || k > b || b >= (int64_t(1) << 31) || n >= (int64_t(1) << 31)) return PAMM_ERR_INVALID_ARG;
     if (k > kMaxGenerators) return PAMM_ERR_UNSUPPORTED;
     if (n % per_chunk(dt) != 0) return PAMM_ERR_UNSUPPORTED;
-    int tg = 1;
-    while (tg < 8 && 32 * tg < k) tg *= 2;
-    p->tg = tg;
-    p->ncb = int((k + 32 * tg - 1) / (32 * tg));
-    // Memory-bound shapes (k <= 128): one token fragment per wave and as many waves per workgroup as still give
-    // every CU a workgroup.  Compute-bound shapes: two token fragments per wave halve the LDS reads per MFMA.
-    const int64_t tiles256 = (b + 255) / 256;
-    p->tt = (k > 128 && tiles256 * p->ncb >= 192) ? 2 : 1;
-    const int tt_env = env_int("PAMM_SCORE_TT");
-    if (tt_env == 1 || tt_env == 2) p->tt = tt_env;
-    if (p->tt == 2) {
-        p->nw = 4;
-    } else {
-        p->nw = 8;
-        while (p->nw > 2 && ((b + 32 * p->nw - 1) / (32 * p->nw)) * p->ncb < 224) p->nw /= 2;
-        const int nw_env = env_int("PAMM_SCORE_NW");
-        if (nw_env == 2 || nw_env == 4 || nw_env == 8) p->nw = nw_env;
+    // A workgroup scores 32*nw tokens (nw waves, 32 each) against a column block of 32*tg generators.  Wanted, in
+    // this order: enough workgroups to give every CU one (at least 224), at least four waves in each (one per SIMD,
+    // better eight), and column blocks as wide as the generators allow (fewer passes over X; with a single block
+    // the kernel also takes the final decision).  When the widest block leaves CUs idle or SIMDs empty (few tokens,
+    // many generators), narrower blocks are tried, down to a quarter of the widest.
+    int tg_max = 1;
+    while (tg_max < 8 && 32 * tg_max < k) tg_max *= 2;
+    auto blocks = [&](int tg) { return (k + 32 * tg - 1) / (32 * tg); };
+    auto tiles = [&](int nw) { return (b + 32 * nw - 1) / (32 * nw); };
+    int tg = tg_max, nw = 0;
+    for (int t = tg_max; t >= 1 && t * 4 >= tg_max && nw == 0; t /= 2)
+        for (int w = 8; w >= 4 && nw == 0; w /= 2)
+            if (tiles(w) * blocks(t) >= 224) { tg = t; nw = w; }
+    if (nw == 0) {               // nothing fills the chip: widest blocks, as many waves as still give every CU a workgroup
+        nw = 8;
+        while (nw > 2 && tiles(nw) * blocks(tg) < 224) nw /= 2;
     }
+    const int tg_env = env_int("PAMM_SCORE_TG");
+    if ((tg_env == 1 || tg_env == 2 || tg_env == 4 || tg_env == 8) && tg_env <= tg_max) tg = tg_env;
+    const int nw_env = env_int("PAMM_SCORE_NW");
+    if (nw_env == 2 || nw_env == 4 || nw_env == 8) nw = nw_env;
+    p->tg = tg;
+    p->ncb = int(blocks(tg));
+    p->tt = 1;
+    p->nw = nw;
     const int64_t tile_tokens = 32 * p->tt * p->nw;
     p->row_tiles = (b + tile_tokens - 1) / tile_tokens;
     size_t o = 0;
