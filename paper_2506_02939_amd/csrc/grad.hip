@@ -20,7 +20,8 @@ namespace pamm {
 // L2): pass 1 counts rows with key < j (start of generator j's list) and key == j per wave, pass 2
 // compacts the matching row numbers with ballots, which keeps them in increasing order.
 //
-// The sorted list (perm, alpha_s, key_s) is later cut into chunks of P consecutive positions; a
+// The sorted list holds one 16-byte entry per row: {row number, alpha_i (bits), generator, 0}.  It is later
+// cut into chunks of P consecutive positions; a
 // "piece" is a maximal run of one generator inside one chunk and is numbered chunk + generator.
 // Piece numbers are unique, increase along the list and stay below ceil(b/P) + k.  Generator j owns
 // the pieces [seg_start_j / P + j, (seg_end_j - 1) / P + j].
@@ -41,16 +42,18 @@ __device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, int i0,
     }
 }
 
-// Entries b .. roundup(b,16)-1 of the sorted lists: a valid row, weight 0, the key of the last real entry.
-__device__ __forceinline__ void pad_lists(int32_t* __restrict__ perm, float* __restrict__ alpha_s, int32_t* __restrict__ key_s,
-                                          int b, int last_key) {
-    for (int q = b; q < (b + 15) / 16 * 16; ++q) { perm[q] = 0; alpha_s[q] = 0.f; key_s[q] = last_key; }
+__device__ __forceinline__ u32x4_t list_entry(int row, float a, int key) {
+    return u32x4_t{uint32_t(row), __float_as_uint(a), uint32_t(key), 0u};
+}
+
+// Entries b .. roundup(b,16)-1 of the sorted list: a valid row, weight 0, the key of the last real entry.
+__device__ __forceinline__ void pad_list(u32x4_t* __restrict__ list, int b, int last_key) {
+    for (int q = b; q < (b + 15) / 16 * 16; ++q) list[q] = list_entry(0, 0.f, last_key);
 }
 
 // Generic version: two passes over f from L2, any b.
 __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                       int P, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
-                                                       int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
+                                                       int P, u32x4_t* __restrict__ list, int32_t* __restrict__ sbase,
                                                        int32_t* __restrict__ snum) {
     const int j = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -99,9 +102,7 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (hit[c]) {
-                    perm[pos + before + within] = i0 + c;
-                    alpha_s[pos + before + within] = alpha[i0 + c];
-                    key_s[pos + before + within] = j;
+                    list[pos + before + within] = list_entry(i0 + c, alpha[i0 + c], j);
                     ++within;
                 }
             }
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
     if (tid == 0) {
         sbase[j] = seg_start / P + j;
         snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
-        if (count > 0 && seg_start + count == b) pad_lists(perm, alpha_s, key_s, b, j);
+        if (count > 0 && seg_start + count == b) pad_list(list, b, j);
     }
 }
 
@@ -119,8 +120,7 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
 // registers, so f is read once and both passes run out of registers.
 template <int NV>
 __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                     int P, int32_t* __restrict__ perm, float* __restrict__ alpha_s,
-                                                     int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
+                                                     int P, u32x4_t* __restrict__ list, int32_t* __restrict__ sbase,
                                                      int32_t* __restrict__ snum) {
     const int j = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -167,9 +167,7 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     if (hit[c]) {
-                        perm[pos + before + within] = i0 + c;
-                        alpha_s[pos + before + within] = alpha[i0 + c];
-                        key_s[pos + before + within] = j;
+                        list[pos + before + within] = list_entry(i0 + c, alpha[i0 + c], j);
                         ++within;
                     }
                 }
@@ -180,93 +178,96 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
     if (tid == 0) {
         sbase[j] = seg_start / P + j;
         snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
-        if (count > 0 && seg_start + count == b) pad_lists(perm, alpha_s, key_s, b, j);
+        if (count > 0 && seg_start + count == b) pad_list(list, b, j);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Grouping in O(b) for k <= 2048: a counting sort over slices of 4096 rows.
+// Grouping in O(b) for k <= 2048: a counting sort over slices of 4*NT rows (NT threads per workgroup).
 //   k_hist     one workgroup per slice: histogram of the slice's keys (LDS atomics), written to table[slice][j]
 //   k_scatter  one workgroup per slice: start of every generator's list (sum over all slices, scanned over j), plus
 //              the rows of earlier slices, plus the rows of earlier waves of this slice; then every row takes the
-//              next free position of its (wave, generator) counter.
+//              next free position of its (wave, generator) counter and writes its 16-byte list entry.
 // Inside a wave the order of equal keys is the order in which the LDS unit serves the lanes of one atomic
 // instruction; it does not depend on timing, so the list, and every sum formed from it, is the same on every call.
-constexpr int kSliceRows = 4096;
-constexpr int kScatterMaxK = 2048;     // 18 * k ints of LDS
+constexpr int kScatterMaxK = 2048;     // (NT/64 + 2) * k ints of LDS
 
-__global__ __launch_bounds__(1024) void k_hist(const int32_t* __restrict__ f, int b, int k, int32_t* __restrict__ table) {
+template <int NT>
+__global__ __launch_bounds__(NT) void k_hist(const int32_t* __restrict__ f, int b, int k, int32_t* __restrict__ table) {
     extern __shared__ int hist[];
     const int tid = threadIdx.x;
-    for (int j = tid; j < k; j += 1024) hist[j] = 0;
-    __syncthreads();
     int key[4];
-    const int i0 = blockIdx.x * kSliceRows + 4 * tid;
-    load_keys(f, i0, b, k, key);
+    load_keys(f, blockIdx.x * (4 * NT) + 4 * tid, b, k, key);
+    for (int j = tid; j < k; j += NT) hist[j] = 0;
+    __syncthreads();
 #pragma unroll
     for (int c = 0; c < 4; ++c)
         if (key[c] < k) atomicAdd(&hist[key[c]], 1);
     __syncthreads();
-    for (int j = tid; j < k; j += 1024) table[size_t(blockIdx.x) * k + j] = hist[j];
+    for (int j = tid; j < k; j += NT) table[size_t(blockIdx.x) * k + j] = hist[j];
 }
 
-__global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                  int P, int nslices, const int32_t* __restrict__ table,
-                                                  int32_t* __restrict__ perm, float* __restrict__ alpha_s,
-                                                  int32_t* __restrict__ key_s, int32_t* __restrict__ sbase,
-                                                  int32_t* __restrict__ snum) {
+template <int NT>
+__global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
+                                                int P, int nslices, const int32_t* __restrict__ table,
+                                                u32x4_t* __restrict__ list, int32_t* __restrict__ sbase,
+                                                int32_t* __restrict__ snum) {
+    constexpr int NWV = NT / 64;
     extern __shared__ int lds[];
-    int* wh = lds;                 // [16][k]  per-wave counts, later per-wave next free position inside the generator's list
-    int* tot = lds + 16 * k;       // [k]      rows per generator (whole batch), later start of the generator's list
-    int* bef = lds + 17 * k;       // [k]      rows per generator in earlier slices
-    __shared__ int wsum[16];
+    int* wh = lds;                 // [NWV][k] per-wave counts, later per-wave next free position inside the generator's list
+    int* tot = lds + NWV * k;      // [k]      rows per generator (whole batch), later start of the generator's list
+    int* bef = tot + k;            // [k]      rows per generator in earlier slices
+    __shared__ int wsum[NWV];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int slice = blockIdx.x;
 
     // every global load of the kernel is issued up front (keys, weights, this thread's share of the table), so the
     // kernel pays one memory latency, not one per phase
     int key[4];
-    const int i0 = slice * kSliceRows + 4 * tid;      // wave w owns rows [256 w, 256 w + 256) of the slice
+    const int i0 = slice * (4 * NT) + 4 * tid;        // wave w owns rows [256 w, 256 w + 256) of the slice
     load_keys(f, i0, b, k, key);
     float al[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) al[c] = alpha[min(i0 + c, b - 1)];
     // rows of every generator in earlier slices / in all slices: column sums of the table, taken in parallel by all
-    // threads (each sums a strip of slices for one generator, two generators per thread when k > 1024)
-    const int strips = k <= 1024 ? 1024 / max(k, 1) : 1;            // threads per generator (power-of-two k: exact)
-    int before[2] = {0, 0}, total[2] = {0, 0};
+    // threads: `strips` threads per generator when there are fewer generators than threads, each summing every
+    // strips-th slice; otherwise every thread sums whole columns for the generators tid, tid + NT, ...
+    constexpr int GPT = (kScatterMaxK + NT - 1) / NT;          // generators per thread at most
+    const int strips = k <= NT ? NT / k : 1;
+    int before[GPT], total[GPT];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int j = h * 1024 + (strips > 1 ? tid % k : tid);
+    for (int h = 0; h < GPT; ++h) {
+        before[h] = total[h] = 0;
+        const int j = h * NT + (strips > 1 ? tid % k : tid);
         const int strip = strips > 1 ? tid / k : 0;
-        if (j < k && strip < strips && (h == 0 || k > 1024)) {
-            for (int s = strip; s < nslices; s += strips) {
-                const int c = table[size_t(s) * k + j];
-                before[h] += s < slice ? c : 0;
+        if (j < k && strip < strips && (h == 0 || k > NT)) {
+            for (int sl = strip; sl < nslices; sl += strips) {
+                const int c = table[size_t(sl) * k + j];
+                before[h] += sl < slice ? c : 0;
                 total[h] += c;
             }
         }
     }
 
-    for (int q = tid; q < 18 * k; q += 1024) wh[q] = 0;      // wh, tot and bef are contiguous
+    for (int q = tid; q < (NWV + 2) * k; q += NT) wh[q] = 0;      // wh, tot and bef are contiguous
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < 4; ++c)
         if (key[c] < k) atomicAdd(&wh[wave * k + key[c]], 1);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int j = h * 1024 + (strips > 1 ? tid % k : tid);
+    for (int h = 0; h < GPT; ++h) {
+        const int j = h * NT + (strips > 1 ? tid % k : tid);
         const int strip = strips > 1 ? tid / k : 0;
-        if (j < k && strip < strips && (h == 0 || k > 1024)) {
+        if (j < k && strip < strips && (h == 0 || k > NT)) {
             atomicAdd(&tot[j], total[h]);
             atomicAdd(&bef[j], before[h]);
         }
     }
     __syncthreads();
-    for (int j = tid; j < k; j += 1024) {
+    for (int j = tid; j < k; j += NT) {
         int run = bef[j];
 #pragma unroll
-        for (int w = 0; w < 16; ++w) {
+        for (int w = 0; w < NWV; ++w) {
             const int c = wh[w * k + j];
             wh[w * k + j] = run;
             run += c;
@@ -274,9 +275,9 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
     }
     __syncthreads();
 
-    // exclusive scan of tot[] over the generators, 1024 at a time
+    // exclusive scan of tot[] over the generators, NT at a time
     int carry = 0;
-    for (int base = 0; base < k; base += 1024) {
+    for (int base = 0; base < k; base += NT) {
         const int j = base + tid;
         const int x = j < k ? tot[j] : 0;
         int incl = x;
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
         __syncthreads();
         int wpre = 0, all = 0;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) {
+        for (int w = 0; w < NWV; ++w) {
             const int v = wsum[w];
             wpre += w < wave ? v : 0;
             all += v;
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
             if (slice == 0) {
                 sbase[j] = start / P + j;
                 snum[j] = x > 0 ? (start + x - 1) / P - start / P + 1 : 0;
-                if (x > 0 && start + x == b) pad_lists(perm, alpha_s, key_s, b, j);      // j owns the end of the list
+                if (x > 0 && start + x == b) pad_list(list, b, j);      // j owns the end of the list
             }
         }
         carry += all;
@@ -311,9 +312,7 @@ __global__ __launch_bounds__(1024) void k_scatter(const int32_t* __restrict__ f,
     for (int c = 0; c < 4; ++c) {
         if (key[c] < k) {
             const int pos = tot[key[c]] + atomicAdd(&wh[wave * k + key[c]], 1);
-            perm[pos] = i0 + c;
-            alpha_s[pos] = al[c];
-            key_s[pos] = key[c];
+            list[pos] = list_entry(i0 + c, al[c], key[c]);
         }
     }
 }
@@ -359,8 +358,7 @@ template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
 // Workgroup = 4 waves that share a chunk of the list and sit side by side along the row: wave w covers W
 // consecutive 512-column groups, so the workgroup reads 4*W KiB of every row at (nearly) the same time.
 template <typename TR, int W>
-__global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const int32_t* __restrict__ perm,
-                                                  const float* __restrict__ alpha_s, const int32_t* __restrict__ key_s, int b,
+__global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const u32x4_t* __restrict__ list, int b,
                                                   int P, int mch, int m, int wgcols, float* __restrict__ partial) {
     const int chunk = blockIdx.x / wgcols, wc = blockIdx.x % wgcols;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -377,7 +375,7 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     for (int w = 0; w < W; ++w)
 #pragma unroll
         for (int q = 0; q < 8; ++q) acc[w][q] = 0.f;
-    int cur = __builtin_amdgcn_readfirstlane(key_s[s0]);
+    int cur = __builtin_amdgcn_readfirstlane(int(list[s0].z));
 
     auto flush = [&](int key) {
 #pragma unroll
@@ -396,31 +394,30 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     // Rows are fetched in groups of U, two groups ahead of the one being summed.  Every step of the loop issues
     // exactly the same number of loads whatever path it takes (positions past the end of the chunk are clamped
     // onto its last group, which is in cache by then), so the wait before a group's sums only has to cover that
-    // group and the two younger ones stay in flight.  The sorted lists are padded to a multiple of 16 entries
-    // (weight 0, last key, a valid row), so a group never needs a guard.  The row numbers of a group are fetched
-    // one step before its loads are issued.
+    // group and the two younger ones stay in flight.  The sorted list is padded to a multiple of 16 entries
+    // (weight 0, last key, a valid row), so a group never needs a guard.
 #ifndef PAMM_CONTRACT_U
 #define PAMM_CONTRACT_U 0
 #endif
     constexpr int U = PAMM_CONTRACT_U ? PAMM_CONTRACT_U : ((RowLoad<TR>::kGroup / W) < 2 ? 2 : (RowLoad<TR>::kGroup / W));
     static_assert(16 % (2 * U) == 0, "a chunk must be a whole number of group pairs");
     const int last = (s1 + 2 * U - 1) / (2 * U) * (2 * U) - U;      // start of the chunk's last group
-    auto rows_of = [&](int (&row)[U], int s) {
+    // list entries (row number, weight, generator: wave-uniform, so they travel through scalar registers)
+    auto entries_of = [&](int (&row)[U], float (&a)[U], int (&key)[U], int s) {
         s = min(s, last);
 #pragma unroll
-        for (int u = 0; u < U; ++u) row[u] = __builtin_amdgcn_readfirstlane(perm[s + u]);
+        for (int u = 0; u < U; ++u) {
+            const u32x4_t e = list[s + u];
+            row[u] = __builtin_amdgcn_readfirstlane(int(e.x));
+            a[u] = __uint_as_float(__builtin_amdgcn_readfirstlane(e.y));
+            key[u] = __builtin_amdgcn_readfirstlane(int(e.z));
+        }
     };
-    auto issue = [&](RowLoad<TR> (&v)[U][W], float (&a)[U], int (&key)[U], const int (&row)[U], int s) {
-        s = min(s, last);
+    auto issue = [&](RowLoad<TR> (&v)[U][W], const int (&row)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int w = 0; w < W; ++w) v[u][w].load(dY + size_t(row[u]) * mch, ch[w], mch);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            a[u] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(alpha_s[s + u])));
-            key[u] = __builtin_amdgcn_readfirstlane(key_s[s + u]);
-        }
     };
     auto consume = [&](const RowLoad<TR> (&v)[U][W], const float (&a)[U], const int (&key)[U]) {
         if (key[0] == cur && key[U - 1] == cur) {          // the list is sorted: the whole group belongs to `cur`
@@ -437,22 +434,28 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
             }
         }
     };
+    // a: group being summed / next to be issued into the same registers; the entries of a group are fetched when the
+    // previous group in the same registers is issued, one step before they are needed
     RowLoad<TR> va[U][W], vb[U][W];
-    float aa[U], ab[U];
-    int ka[U], kb[U], ra[U], rb[U];
-    rows_of(ra, s0);
-    rows_of(rb, s0 + U);
-    issue(va, aa, ka, ra, s0);
-    issue(vb, ab, kb, rb, s0 + U);
-    rows_of(ra, s0 + 2 * U);
-    rows_of(rb, s0 + 3 * U);
+    float aa[U], ab[U], na[U], nb[U];
+    int ka[U], kb[U], ra[U], rb[U], nka[U], nkb[U], nra[U], nrb[U];
+    entries_of(ra, aa, ka, s0);
+    entries_of(rb, ab, kb, s0 + U);
+    issue(va, ra);
+    issue(vb, rb);
+    entries_of(nra, na, nka, s0 + 2 * U);
+    entries_of(nrb, nb, nkb, s0 + 3 * U);
     for (int s = s0; s < s1; s += 2 * U) {
         consume(va, aa, ka);
-        issue(va, aa, ka, ra, s + 2 * U);
-        rows_of(ra, s + 4 * U);
+        issue(va, nra);
+#pragma unroll
+        for (int u = 0; u < U; ++u) { aa[u] = na[u]; ka[u] = nka[u]; }
+        entries_of(nra, na, nka, s + 4 * U);
         consume(vb, ab, kb);
-        issue(vb, ab, kb, rb, s + 3 * U);
-        rows_of(rb, s + 5 * U);
+        issue(vb, nrb);
+#pragma unroll
+        for (int u = 0; u < U; ++u) { ab[u] = nb[u]; kb[u] = nkb[u]; }
+        entries_of(nrb, nb, nkb, s + 5 * U);
     }
     flush(cur);
 }
@@ -646,16 +649,14 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct GradBuffers {
-    int32_t *perm, *key, *sbase, *snum, *table;
-    float *alpha_s, *partial;
-    u32x4_t *ct, *bt;
+    int32_t *sbase, *snum, *table;
+    float* partial;
+    u32x4_t *list, *ct, *bt;
 };
 
 static GradBuffers carve(const GradPlan& pl, char* ws) {
     GradBuffers g;
-    g.perm = reinterpret_cast<int32_t*>(ws + pl.off_perm);
-    g.alpha_s = reinterpret_cast<float*>(ws + pl.off_alpha);
-    g.key = reinterpret_cast<int32_t*>(ws + pl.off_key);
+    g.list = reinterpret_cast<u32x4_t*>(ws + pl.off_list);
     g.sbase = reinterpret_cast<int32_t*>(ws + pl.off_sbase);
     g.snum = reinterpret_cast<int32_t*>(ws + pl.off_snum);
     g.table = reinterpret_cast<int32_t*>(ws + pl.off_table);
@@ -671,13 +672,19 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
     {
         ScopedSpan span(kGroup, s);
         if (k <= kScatterMaxK) {
-            const int nslices = (b + kSliceRows - 1) / kSliceRows;
-            hipLaunchKernelGGL(k_hist, dim3(nslices), dim3(1024), size_t(k) * 4, s, f, b, k, g.table);
-            hipLaunchKernelGGL(k_scatter, dim3(nslices), dim3(1024), size_t(18) * k * 4, s, f, alpha, b, k, pl.piece_rows, nslices,
-                               g.table, g.perm, g.alpha_s, g.key, g.sbase, g.snum);
+            const int nslices = int(pl.nslices);
+            if (pl.slice_rows == 1024) {
+                hipLaunchKernelGGL(k_hist<256>, dim3(nslices), dim3(256), size_t(k) * 4, s, f, b, k, g.table);
+                hipLaunchKernelGGL(k_scatter<256>, dim3(nslices), dim3(256), size_t(4 + 2) * k * 4, s, f, alpha, b, k, pl.piece_rows,
+                                   nslices, g.table, g.list, g.sbase, g.snum);
+            } else {
+                hipLaunchKernelGGL(k_hist<1024>, dim3(nslices), dim3(1024), size_t(k) * 4, s, f, b, k, g.table);
+                hipLaunchKernelGGL(k_scatter<1024>, dim3(nslices), dim3(1024), size_t(16 + 2) * k * 4, s, f, alpha, b, k,
+                                   pl.piece_rows, nslices, g.table, g.list, g.sbase, g.snum);
+            }
         } else {
 #define PAMM_LAUNCH_GROUP(KERNEL) \
-    hipLaunchKernelGGL(KERNEL, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, g.perm, g.alpha_s, g.key, g.sbase, g.snum)
+    hipLaunchKernelGGL(KERNEL, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, g.list, g.sbase, g.snum)
         const int nv = (b + 4095) / 4096;      // int4 loads per lane when 16 waves share the rows
         if (nv <= 1) PAMM_LAUNCH_GROUP(k_group_regs<1>);
         else if (nv <= 2) PAMM_LAUNCH_GROUP(k_group_regs<2>);
@@ -693,8 +700,8 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
         ScopedSpan span(kContract, s);
         const dim3 grid((unsigned)(pl.chunks * pl.wg_cols));
 #define PAMM_LAUNCH_CONTRACT(WV) \
-    hipLaunchKernelGGL((k_contract<TR, WV>), grid, dim3(256), 0, s, (const u32x4_t*)dY, g.perm, g.alpha_s, g.key, b, pl.piece_rows, \
-                       mch, m, pl.wg_cols, g.partial)
+    hipLaunchKernelGGL((k_contract<TR, WV>), grid, dim3(256), 0, s, (const u32x4_t*)dY, g.list, b, pl.piece_rows, mch, m, \
+                       pl.wg_cols, g.partial)
         if (pl.wave_groups == 1) PAMM_LAUNCH_CONTRACT(1);
         else if (pl.wave_groups == 2) PAMM_LAUNCH_CONTRACT(2);
         else PAMM_LAUNCH_CONTRACT(3);

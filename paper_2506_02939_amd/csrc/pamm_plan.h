@@ -93,7 +93,9 @@ struct GradPlan {
     int wave_groups;      // W: 512-column groups per wave (1..3); a workgroup of 4 waves covers 4*W groups of a row
     int wg_cols;          // workgroups side by side along a row: ceil(col_groups / (4*W))
     int64_t kpad;         // k rounded up to a multiple of 16 (a whole number of MFMA steps for both element types)
-    size_t off_perm, off_alpha, off_key, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
+    int slice_rows;       // rows per slice of the counting sort (1024 or 4096)
+    int64_t nslices;      // ceil(b / slice_rows)
+    size_t off_list, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
 };
 
 inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, GradPlan* p) {
@@ -122,13 +124,15 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     p->chunks = (b + P - 1) / P;
     p->nslots = p->chunks + k;
     p->kpad = (k + 15) / 16 * 16;
+    // Counting sort of the rows by generator: short slices spread the scattered list writes over many CUs, but every
+    // slice's workgroup sums the whole table of slice histograms (slices x k entries), so that table must stay small.
+    p->slice_rows = ((b + 1023) / 1024) * k <= 4096 ? 1024 : 4096;
+    p->nslices = (b + p->slice_rows - 1) / p->slice_rows;
     size_t o = 0;
-    p->off_perm = o;    o = align_up(o + size_t(b + 16) * 4, 256);      // the sorted lists are padded to a multiple of 16
-    p->off_alpha = o;   o = align_up(o + size_t(b + 16) * 4, 256);
-    p->off_key = o;     o = align_up(o + size_t(b + 16) * 4, 256);
+    p->off_list = o;    o = align_up(o + size_t(b + 16) * 16, 256);     // 16-byte entries, padded to a multiple of 16 entries
     p->off_sbase = o;   o = align_up(o + size_t(k) * 4, 256);
     p->off_snum = o;    o = align_up(o + size_t(k) * 4, 256);
-    p->off_table = o;   o = align_up(o + size_t((b + 4095) / 4096) * size_t(k) * 4, 256);    // per-slice histograms
+    p->off_table = o;   o = align_up(o + size_t(p->nslices) * size_t(k) * 4, 256);           // per-slice histograms
     p->off_partial = o; o = align_up(o + size_t(p->nslots) * size_t(m) * 4, 256);
     p->off_ct = o;      o = align_up(o + size_t(n) * size_t(p->kpad) * elem_bytes(dt), 256);
     p->off_bt = o;      o = align_up(o + size_t(m) * size_t(p->kpad) * elem_bytes(dt), 256);
