@@ -7,8 +7,8 @@
  * It shares no code, header, table or helper with the HIP library.
  *
  * What it follows (Point-Approximate Matrix Multiplication, Sec. 3.2 and
- * Algorithm 1, at tolerance eps = infinity, i.e. no row is ever dropped and the
- * normalisation factor beta is 1):
+ * Algorithm 1; the tolerance eps may be infinite, in which case no row is ever
+ * dropped and the normalisation factor beta is 1):
  *
  *   Compress(A, k):   I   = k row indices, uniform without replacement   (Alg. 1, Compress, "Sample indices")
  *                     C_j = A[I_j, :]                                     (Alg. 1, generators)
@@ -16,9 +16,12 @@
  *                     f(i) = argmin_j ||A_i - alpha(i,j) C_j||_2
  *                          = argmax_j |csim(A_i, C_j)|                    (Lemma 1)
  *                     alpha_i = alpha(i, f(i))
+ *                     e_i = ||A_i - alpha_i C_f(i)||_2 ;  alpha_i <- 0 where
+ *                     e_i > eps ||A_i||_2                                 (Eq. 2, neighbourhood condition)
+ *                     eta = number of rows dropped, beta = b / (b - eta)  (Sec. 3.2, "Normalization factor beta")
  *   ApproxMM(C, alpha, f, B):
  *                     Btilde_j = sum_{i : f(i) = j} alpha_i B_i           (Sec. 3.2, "Approximate Matrix Multiplication")
- *                     Otilde   = C^T Btilde                               (Alg. 1, ApproxMM)
+ *                     Otilde   = beta C^T Btilde                          (Alg. 1, ApproxMM; beta as above)
  *
  * Readings taken where the paper is silent or inconsistent:
  *   - Alg. 1 prints argmax(csim) while the definition is argmin residual and
@@ -30,6 +33,10 @@
  *   - a zero generator (||C_j|| = 0) scores 0 and yields alpha = 0; a zero row
  *     scores 0 everywhere, so f = 0 and alpha = 0.  No NaN/Inf is produced.
  *   - f is 0-based here (1-based in the paper).
+ *   - Alg. 1 prints the neighbourhood test as e > eps; Eq. 2 has e > eps ||A_i||.
+ *     Eq. 2 (relative) is taken.  A dropped row keeps its f (Alg. 1 only zeroes
+ *     alpha).  If every row is dropped beta is undefined in the paper; 0 here,
+ *     so that Otilde = 0.
  *   - the sampler is specified, because the paper only says "uniformly without
  *     replacement": splitmix64 seeded with `seed`; draw t (t = 0..k-1) takes
  *     r = t + bounded(b - t) where bounded(u) is unbiased rejection sampling
@@ -45,6 +52,11 @@
  *   alpha        orthogonality of the residual to C_f(i); Pythagoras; alpha = 1 on generators.
  *   Btilde, dW   k = b, C = A gives exactly A^T B; regrouping identity against A~^T B;
  *                k = 1 closed form; error bound of Sec. 3.2.1.
+ *   eps, beta    eps = infinity reproduces the unconditioned path; kept rows checked against
+ *                Eq. 2 written out in numpy; eps = 0 is uniform column-row sampling
+ *                (Sec. 4.1), whose closed form b/k sum_{i in I} A_i^T B_i and whose
+ *                unbiasedness over all k-subsets are checked by enumeration; error bound of
+ *                Sec. 3.2.1 with dropped rows.
  *
  * Element types: 0 = IEEE binary32, 1 = bfloat16 (raw 16-bit patterns),
  * 2 = IEEE binary64.  Decoding to double is exact for all three.
@@ -152,12 +164,16 @@ int pamm_oracle_sample(int64_t b, int64_t k, uint64_t seed, int32_t *idx)
  *          best   b doubles: s(i, f(i))                   } diagnostics that let a test apply the
  *          second b doubles: max_{j != f(i)} s(i,j)       } "near-tie" exclusion; -1 when k = 1
  *          jsecond b int32: lowest j != f(i) attaining `second`, -1 when k = 1
- * Any of best/second/jsecond may be NULL.
+ *          resid   b doubles: e_i = ||A_i - alpha_i C_f(i)||_2 before the mask       } Eq. 2, both
+ *          rownorm b doubles: ||A_i||_2                                               } sides
+ *          eta     number of rows dropped by the neighbourhood condition e_i > eps ||A_i||_2
+ * eps < 0 stands for eps = infinity (no row dropped).  Any of best/second/jsecond/resid/rownorm/eta may be NULL.
  */
 int pamm_oracle_compress(const void *A, int dtype, int64_t b, int64_t n, int64_t k,
-                         const int32_t *idx,
+                         const int32_t *idx, double eps,
                          double *C, int32_t *f, double *alpha,
-                         double *best, double *second, int32_t *jsecond)
+                         double *best, double *second, int32_t *jsecond,
+                         double *resid, double *rownorm, int64_t *eta)
 {
     if (!A || !idx || !C || !f || !alpha || b < 1 || n < 1 || k < 1 || k > b) return -1;
     for (int64_t j = 0; j < k; ++j)
@@ -165,6 +181,7 @@ int pamm_oracle_compress(const void *A, int dtype, int64_t b, int64_t n, int64_t
 
     double *cn2 = (double *)malloc((size_t)k * sizeof *cn2);
     if (!cn2) return -1;
+    int64_t dropped = 0;
 
     for (int64_t j = 0; j < k; ++j) {
         double acc = 0.0;
@@ -198,15 +215,40 @@ int pamm_oracle_compress(const void *A, int dtype, int64_t b, int64_t n, int64_t
                 }
             }
             f[i] = (int32_t)j1;
-            alpha[i] = (cn2[j1] > 0.0) ? d1 / cn2[j1] : 0.0;           /* Eq. 1 */
+            double a = (cn2[j1] > 0.0) ? d1 / cn2[j1] : 0.0;           /* Eq. 1 */
             if (best) best[i] = s1;
             if (second) second[i] = s2;
             if (jsecond) jsecond[i] = (int32_t)j2;
+
+            /* Eq. 2: the residual of the representative, formed as the vector it is */
+            const double *c = C + j1 * n;
+            double e2 = 0.0, a2 = 0.0;
+            for (int64_t l = 0; l < n; ++l) {
+                double r = row[l] - a * c[l];
+                e2 += r * r;
+                a2 += row[l] * row[l];
+            }
+            double e = sqrt(e2), na = sqrt(a2);
+            if (resid) resid[i] = e;
+            if (rownorm) rownorm[i] = na;
+            if (eps >= 0.0 && e > eps * na) {                          /* neighbourhood condition fails: drop the row */
+                a = 0.0;
+#pragma omp atomic
+                dropped += 1;
+            }
+            alpha[i] = a;
         }
         free(row);
     }
     free(cn2);
+    if (eta) *eta = dropped;
     return 0;
+}
+
+/* beta = b / (b - eta) (Sec. 3.2); 0 when every row was dropped */
+double pamm_oracle_beta(int64_t b, int64_t eta)
+{
+    return (eta < b) ? (double)b / (double)(b - eta) : 0.0;
 }
 
 /* --------------------------------------------------------------- ApproxMM */
@@ -214,11 +256,12 @@ int pamm_oracle_compress(const void *A, int dtype, int64_t b, int64_t n, int64_t
 /*
  * Inputs : C (k x n doubles), f (b), alpha (b doubles), B (b x m, element type dtype).
  * Outputs: Btilde k x m doubles, Btilde_j = sum_{i: f(i)=j} alpha_i B_i, rows added in increasing i;
- *          O      n x m doubles, O = C^T Btilde, plain triple loop with j innermost-in-order.
+ *          O      n x m doubles, O = beta C^T Btilde, plain triple loop with j innermost-in-order
+ *                 (beta = 1 when no row was dropped).
  */
 int pamm_oracle_grad(const double *C, const int32_t *f, const double *alpha,
                      const void *B, int dtype,
-                     int64_t b, int64_t n, int64_t k, int64_t m,
+                     int64_t b, int64_t n, int64_t k, int64_t m, double beta,
                      double *Btilde, double *O)
 {
     if (!C || !f || !alpha || !B || !Btilde || !O || b < 1 || n < 1 || k < 1 || m < 1) return -1;
@@ -254,6 +297,7 @@ int pamm_oracle_grad(const double *C, const int32_t *f, const double *alpha,
             const double *bt = Btilde + j * m;
             for (int64_t c = 0; c < m; ++c) out[c] += cjl * bt[c];
         }
+        for (int64_t c = 0; c < m; ++c) out[c] *= beta;
     }
     return 0;
 }

@@ -43,9 +43,12 @@ def _load():
         lib.pamm_oracle_splitmix64.argtypes = [ctypes.c_uint64, i64, ctypes.POINTER(ctypes.c_uint64)]
         lib.pamm_oracle_sample.argtypes = [i64, i64, ctypes.c_uint64, i32p]
         lib.pamm_oracle_sample.restype = ctypes.c_int
-        lib.pamm_oracle_compress.argtypes = [vp, ctypes.c_int, i64, i64, i64, i32p, f64p, i32p, f64p, f64p, f64p, i32p]
+        lib.pamm_oracle_compress.argtypes = [vp, ctypes.c_int, i64, i64, i64, i32p, ctypes.c_double, f64p, i32p, f64p, f64p, f64p,
+                                             i32p, f64p, f64p, ctypes.POINTER(ctypes.c_int64)]
         lib.pamm_oracle_compress.restype = ctypes.c_int
-        lib.pamm_oracle_grad.argtypes = [f64p, i32p, f64p, vp, ctypes.c_int, i64, i64, i64, i64, f64p, f64p]
+        lib.pamm_oracle_beta.argtypes = [i64, i64]
+        lib.pamm_oracle_beta.restype = ctypes.c_double
+        lib.pamm_oracle_grad.argtypes = [f64p, i32p, f64p, vp, ctypes.c_int, i64, i64, i64, i64, ctypes.c_double, f64p, f64p]
         lib.pamm_oracle_grad.restype = ctypes.c_int
         lib.pamm_oracle_score.argtypes = [vp, ctypes.c_int, i64, i64, i64]
         lib.pamm_oracle_score.restype = ctypes.c_double
@@ -118,10 +121,14 @@ class Compressed:
     best: np.ndarray     # b float64, score of the chosen generator
     second: np.ndarray   # b float64, best score among the other generators (-1 if k == 1)
     jsecond: np.ndarray  # b int32, generator attaining `second` (-1 if k == 1)
+    resid: np.ndarray    # b float64, ||A_i - alpha_i C_f(i)||_2 before the neighbourhood mask
+    rownorm: np.ndarray  # b float64, ||A_i||_2
+    eta: int             # rows dropped by the neighbourhood condition
+    beta: float          # b / (b - eta)
 
 
-def compress(X, k: int, seed: int = 0, idx=None) -> Compressed:
-    """Compress(A, k) at eps = infinity.  `idx` overrides the sampler (caller-chosen generators)."""
+def compress(X, k: int, seed: int = 0, idx=None, eps: float = float("inf")) -> Compressed:
+    """Compress(A, k, eps).  `idx` overrides the sampler (caller-chosen generators); eps = inf drops no row."""
     a, code = as_raw(X)
     b, n = a.shape
     idx = sample(b, k, seed) if idx is None else np.ascontiguousarray(idx, dtype=np.int32)
@@ -132,17 +139,25 @@ def compress(X, k: int, seed: int = 0, idx=None) -> Compressed:
     best = np.empty(b, dtype=np.float64)
     second = np.empty(b, dtype=np.float64)
     jsecond = np.empty(b, dtype=np.int32)
+    resid = np.empty(b, dtype=np.float64)
+    rownorm = np.empty(b, dtype=np.float64)
+    eta = ctypes.c_int64(0)
+    eps_c = -1.0 if (eps is None or np.isinf(eps)) else float(eps)
+    if eps_c < 0.0 and not (eps is None or np.isinf(eps)):
+        raise ValueError("eps must be >= 0")
     rc = _load().pamm_oracle_compress(
-        a.ctypes.data_as(ctypes.c_void_p), code, b, n, k, _p(idx, ctypes.c_int32),
+        a.ctypes.data_as(ctypes.c_void_p), code, b, n, k, _p(idx, ctypes.c_int32), eps_c,
         _p(C, ctypes.c_double), _p(f, ctypes.c_int32), _p(alpha, ctypes.c_double),
-        _p(best, ctypes.c_double), _p(second, ctypes.c_double), _p(jsecond, ctypes.c_int32))
+        _p(best, ctypes.c_double), _p(second, ctypes.c_double), _p(jsecond, ctypes.c_int32),
+        _p(resid, ctypes.c_double), _p(rownorm, ctypes.c_double), ctypes.byref(eta))
     if rc != 0:
         raise ValueError("pamm_oracle_compress: bad arguments")
-    return Compressed(idx, C, f, alpha, best, second, jsecond)
+    beta = float(_load().pamm_oracle_beta(b, eta.value))
+    return Compressed(idx, C, f, alpha, best, second, jsecond, resid, rownorm, int(eta.value), beta)
 
 
-def grad(C, f, alpha, dY):
-    """ApproxMM(C, alpha, f, B): returns (Btilde k x m, Otilde n x m), both float64."""
+def grad(C, f, alpha, dY, beta: float = 1.0):
+    """ApproxMM(C, alpha, f, B): returns (Btilde k x m, Otilde = beta C^T Btilde, n x m), both float64."""
     C = np.ascontiguousarray(C, dtype=np.float64)
     f = np.ascontiguousarray(f, dtype=np.int32)
     alpha = np.ascontiguousarray(alpha, dtype=np.float64)
@@ -154,7 +169,7 @@ def grad(C, f, alpha, dY):
     O = np.empty((n, m), dtype=np.float64)
     rc = _load().pamm_oracle_grad(
         _p(C, ctypes.c_double), _p(f, ctypes.c_int32), _p(alpha, ctypes.c_double),
-        y.ctypes.data_as(ctypes.c_void_p), code, b, n, k, m, _p(Bt, ctypes.c_double), _p(O, ctypes.c_double))
+        y.ctypes.data_as(ctypes.c_void_p), code, b, n, k, m, float(beta), _p(Bt, ctypes.c_double), _p(O, ctypes.c_double))
     if rc != 0:
         raise ValueError("pamm_oracle_grad: bad arguments")
     return Bt, O
