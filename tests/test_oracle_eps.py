@@ -41,7 +41,7 @@ def test_kept_rows_are_those_of_the_neighbourhood_condition(oracle, eps):
     e = np.linalg.norm(X - free.alpha[:, None] * C[free.f], axis=1)
     na = np.linalg.norm(X, axis=1)
     margin = e - eps * na
-    clear = np.abs(margin) > 1e-9 * na                       # rows not sitting on the boundary itself
+    clear = (np.abs(margin) > 1e-9 * na) | (e == 0.0)        # not on the boundary itself (a zero residual is unambiguous)
     kept = margin <= 0
     assert clear.all() and np.all(free.alpha != 0)           # continuous data: nobody on the boundary, no zero coefficient
     assert np.array_equal(c.alpha != 0, kept)
