@@ -106,6 +106,26 @@ pamm_status pamm_compress_idx(const void *X, int64_t b, int64_t n, int64_t k, co
                               void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Alg. 1, procedure Compress, with a finite tolerance eps >= 0: the neighbourhood condition of Eq. 2,
+ *   ||X_i - alpha_i C_f(i)||_2 <= eps ||X_i||_2,
+ * is applied to the representative of every row; a row that fails it is dropped, i.e. its alpha is set to 0 (its
+ * f stays: "alpha[e > eps] <- 0").  Eq. 2 (relative to ||X_i||) is taken where Alg. 1 prints the absolute e > eps.
+ * eps = 0 keeps only rows lying exactly on a generator's line: uniform column-row sampling (Sec. 4.1).
+ * eps >= 1 (or +infinity) can drop nothing and is the same as pamm_compress.  Negative or NaN: PAMM_ERR_INVALID_ARG.
+ *   eta    out  DEVICE pointer to one int32 (4-byte aligned): the number of rows dropped.  The normalisation factor
+ *               of Sec. 3.2 is beta = b / (b - eta); pamm_grad_eps applies it.
+ * All other arguments as pamm_compress / pamm_compress_idx.  The test is taken in fp32 (||X_i||^2 comes from the
+ * same pass over X, on the matrix cores) except for rows within 2^-11 ||X_i||^2 of the limit, which are decided in
+ * fp64 like the near-ties of f.
+ */
+pamm_status pamm_compress_eps(const void *X, int64_t b, int64_t n, int64_t k, uint64_t seed, float eps, pamm_dtype dt,
+                              void *C, int32_t *f, float *alpha, int32_t *eta,
+                              void *ws, size_t ws_bytes, void *stream);
+pamm_status pamm_compress_idx_eps(const void *X, int64_t b, int64_t n, int64_t k, const int32_t *idx_dev, float eps,
+                                  pamm_dtype dt, void *C, int32_t *f, float *alpha, int32_t *eta,
+                                  void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Alg. 1, procedure ApproxMM: dW = C^T Btilde with Btilde_j = sum_{i: f(i)=j} alpha_i dY_i.
  *   C      in   k x n, dtype dt          f      in  b int32 in [0,k)        alpha  in  b fp32
  *   dY     in   b x m, dtype dt
@@ -119,6 +139,16 @@ pamm_status pamm_compress_idx(const void *X, int64_t b, int64_t n, int64_t k, co
 pamm_status pamm_grad(const void *C, const int32_t *f, const float *alpha, const void *dY,
                       int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt,
                       float *dW, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * ApproxMM with the normalisation factor of Sec. 3.2: dW = beta C^T Btilde, beta = b / (b - eta) (0 if eta = b), so
+ * that the dropped rows do not bias the estimate.
+ *   eta    in   DEVICE pointer to one int32, as written by pamm_compress_eps on the same stream or earlier
+ * All other arguments as pamm_grad.
+ */
+pamm_status pamm_grad_eps(const void *C, const int32_t *f, const float *alpha, const int32_t *eta, const void *dY,
+                          int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt,
+                          float *dW, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Test/benchmark hook: only the contraction stage of ApproxMM.

@@ -1,4 +1,6 @@
-// pamm_compress / pamm_compress_idx: Alg. 1, procedure Compress, at eps = infinity.
+// pamm_compress / pamm_compress_idx and their _eps forms: Alg. 1, procedure Compress.  With a finite tolerance
+// (Eq. 2) the score kernel also sums ||X_i||^2 from the chunks of X as they pass through its registers, and the
+// final decision drops the rows whose best representative is outside the neighbourhood.
 //
 // Launches on the caller's stream:
 //   k_gather    C_j = X[idx_j] (bit copy), ||C_j||^2 in fp64, a content hash per generator
@@ -65,6 +67,10 @@ struct Best {
         dst[0] = u32x4_t{__float_as_uint(s1), __float_as_uint(d1), __float_as_uint(s2), __float_as_uint(s3)};
         dst[1] = u32x4_t{__float_as_uint(s4), uint32_t(j1) | (uint32_t(jt) << 16), uint32_t(j2) | (uint32_t(j3) << 16), 0u};
     }
+    static __device__ __forceinline__ void store_norm(u32x4_t* dst, float nx) {      // ||X_i||^2 rides in the spare slot
+        reinterpret_cast<float*>(dst + 1)[3] = nx;
+    }
+    static __device__ __forceinline__ float load_norm(const u32x4_t* src) { return __uint_as_float(src[1].w); }
     __device__ __forceinline__ void load(const u32x4_t* src) {
         const u32x4_t p = src[0], q = src[1];
         s1 = __uint_as_float(p.x); d1 = __uint_as_float(p.y); s2 = __uint_as_float(p.z); s3 = __uint_as_float(p.w);
@@ -79,8 +85,10 @@ struct Best {
 template <typename TR>
 __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, const int32_t* __restrict__ idx_in, int b, int nch,
                                                 u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
-                                                double* __restrict__ cn2, unsigned long long* __restrict__ hash) {
+                                                double* __restrict__ cn2, unsigned long long* __restrict__ hash,
+                                                int32_t* __restrict__ eta) {
     const int j = blockIdx.x;
+    if (eta && j == 0 && threadIdx.x == 0) *eta = 0;          // rows dropped by the neighbourhood condition: counted later
     int src = idx_in[j];
     src = src < 0 ? 0 : (src >= b ? b - 1 : src);
     const u32x4_t* xr = X + size_t(src) * nch;
@@ -126,6 +134,16 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
 // waves then share them out (drain_queue, called by the whole workgroup).
 constexpr int kRedoInts = 6;     // row, number of extra candidates (4 = all generators), j1, c1, c2, c3
 
+// Neighbourhood condition (Eq. 2): ||X_i - alpha_i C_f(i)||_2 <= eps ||X_i||_2, i.e. s(i,f(i)) >= (1 - eps^2) ||X_i||^2
+// (the residual of a projection: ||X_i||^2 - s).  keep = 1 - eps^2; keep < 0 switches the test off (eps >= 1 can
+// drop nothing).  In fp32 the test is trusted outside a band of 2^-11 ||X_i||^2 around the limit; inside it the
+// token goes to the fp64 second look, which compares <X_i,C_j>^2 with keep ||X_i||^2 ||C_j||^2 (no division: a row
+// that is an exact copy or power-of-two multiple of its generator passes at eps = 0 without rounding).
+struct Neighbourhood {
+    double keep;           // 1 - eps^2, or negative: no condition
+    int* dropped;          // LDS counter of the workgroup
+};
+
 // Dot products of one row of X with two generators, in fp64, by the whole wave.  This code runs a handful of times
 // per launch, on the critical path of its workgroup: loads go out four chunks per lane at a time (one memory
 // latency for rows of up to 256 chunks), and the code is kept small because all of it misses the instruction cache.
@@ -164,8 +182,15 @@ __device__ __noinline__ void wave_dot2(const u32x4_t* __restrict__ x, const u32x
 // Called by every lane.  Writes f and alpha of the lane's token unless it needs a second look; then it is queued.
 __device__ __forceinline__ void decide_or_queue(const float* __restrict__ inv, const double* __restrict__ cn2,
                                                 const unsigned long long* __restrict__ hash, bool valid, int row, const Best& st,
-                                                int32_t* __restrict__ f, float* __restrict__ alpha, int* q_count, int* q_entries) {
+                                                float nx, const Neighbourhood& nb, int32_t* __restrict__ f,
+                                                float* __restrict__ alpha, int* q_count, int* q_entries) {
     if (!valid) return;
+    bool unsure = false, drop = false;
+    if (nb.keep >= 0.0) {
+        const float lim = float(nb.keep) * nx, band = 0x1p-11f * nx;
+        drop = st.s1 < lim - band;
+        unsure = !drop && st.s1 < lim + band;
+    }
     int ncand = 0, c1 = 0, c2 = 0, c3 = 0;
     if (st.s1 > 0.f) {
         const float thr = st.s1 * (1.f - 0x1p-12f);
@@ -180,9 +205,10 @@ __device__ __forceinline__ void decide_or_queue(const float* __restrict__ inv, c
         }
         if (st.s4 >= thr) ncand = 4;
     }
-    if (ncand == 0) {
+    if (ncand == 0 && !unsure) {
         f[row] = st.j1;
-        alpha[row] = st.d1 * inv[st.j1];
+        alpha[row] = drop ? 0.f : st.d1 * inv[st.j1];
+        if (drop) atomicAdd(nb.dropped, 1);
     } else {
         int* e = q_entries + atomicAdd(q_count, 1) * kRedoInts;
         e[0] = row; e[1] = ncand; e[2] = st.j1; e[3] = c1; e[4] = c2; e[5] = c3;
@@ -192,8 +218,9 @@ __device__ __forceinline__ void decide_or_queue(const float* __restrict__ inv, c
 // Called by the whole workgroup (NWAVES waves) after a barrier that follows the last decide_or_queue.
 template <typename TR, int NWAVES>
 __device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                            const double* __restrict__ cn2, int nch, int k, int32_t* __restrict__ f,
-                                            float* __restrict__ alpha, const int* q_count, const int* q_entries) {
+                                            const double* __restrict__ cn2, int nch, int k, const Neighbourhood& nb,
+                                            int32_t* __restrict__ f, float* __restrict__ alpha, const int* q_count,
+                                            const int* q_entries) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int total = *q_count;
     for (int t = wave; t < total; t += NWAVES) {
@@ -213,7 +240,9 @@ __device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const
             take(ja, da, na);
             if (jb != ja) take(jb, db, nb);
         };
-        if (rn < 4) {
+        if (rn == 0) {
+            eval2(e[2], e[2]);             // only the neighbourhood condition is in doubt
+        } else if (rn < 4) {
             // the named candidates in increasing j; unused slots sort to the end
             constexpr int kNone = 0x7fffffff;
             int a0 = e[2], a1 = e[3], a2 = rn >= 2 ? e[4] : kNone, a3 = rn >= 3 ? e[5] : kNone;
@@ -226,9 +255,16 @@ __device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const
 #pragma unroll 1
             for (int j0 = 0; j0 < k; j0 += 2) eval2(j0, min(j0 + 1, k - 1));
         }
+        bool kept = true;
+        if (nb.keep >= 0.0) {
+            double nx, unused;
+            wave_dot2<TR>(xr, xr, xr, nch, nx, unused);
+            kept = bd * bd >= nb.keep * nx * bc;
+        }
         if (lane == 0) {
             f[row] = bj;
-            alpha[row] = bc > 0.0 ? float(bd / bc) : 0.f;
+            alpha[row] = (kept && bc > 0.0) ? float(bd / bc) : 0.f;
+            if (!kept) atomicAdd(nb.dropped, 1);
         }
     }
 }
@@ -255,8 +291,10 @@ template <typename TR, int TG, int TT, int NW, bool ALIGNED, bool FUSED>
 __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
                                                    const float* __restrict__ inv, const double* __restrict__ cn2,
                                                    const unsigned long long* __restrict__ hash, int b, int nch, int k, int ncb,
-                                                   u32x4_t* __restrict__ cand, int32_t* __restrict__ f, float* __restrict__ alpha) {
+                                                   u32x4_t* __restrict__ cand, int32_t* __restrict__ f, float* __restrict__ alpha,
+                                                   double keep, int32_t* __restrict__ eta) {
     constexpr int NT = 64 * NW;
+    const bool want_norm = keep >= 0.0;           // a finite tolerance: ||X_i||^2 is needed (uniform over the grid)
     constexpr int GB = 32 * TG;          // generators per column block
     constexpr int SS = 8 / TG;           // super-steps per stage
     constexpr int CPS = 8 * SS;          // chunks per generator per stage
@@ -270,7 +308,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 
     __shared__ u32x4_t lds_raw[2 * CBUF + NW * 2 * XSLOT];
     __shared__ __attribute__((aligned(16))) float lds_inv[GB];
-    __shared__ int redo_count;
+    __shared__ int redo_count, drop_count;
     __shared__ int redo_entries[FUSED ? 32 * TT * NW * kRedoInts : 1];   // every token of the tile could need a second look
     u32x4_t* const lds_c = lds_raw;                                         // [2][CBUF]
     const int tid = threadIdx.x;
@@ -280,7 +318,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     const int rt = blockIdx.x / ncb;
     const int gen0 = cb * GB;
 
-    if (tid == 0) redo_count = 0;                  // published by the barriers of the main loop
+    if (tid == 0) { redo_count = 0; drop_count = 0; }          // published by the barriers of the main loop
     for (int t = tid; t < GB; t += NT) {
         const int j = gen0 + t;
         lds_inv[t] = j < k ? inv[j] : -1.f;        // negative marks a slot past the last generator
@@ -301,12 +339,16 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         }
 
     f32x16_t acc[TG][TT];
+    float nrm[TT][4];                              // this lane's share of ||X_i||^2 for the four rows it loads
 #pragma unroll
-    for (int a = 0; a < TG; ++a)
+    for (int t = 0; t < TT; ++t) {
 #pragma unroll
-        for (int t = 0; t < TT; ++t)
+        for (int a = 0; a < TG; ++a)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][t][i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) nrm[t][i] = 0.f;
+    }
 
     const int nstages = (nch + CPS - 1) / CPS;
     const int nss = (nch + 7) / 8;               // super-steps
@@ -354,18 +396,31 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 }
             }
     };
-    auto stash_x = [&](const u32x4_t (&src)[TT][4], int slot) {      // registers -> this wave's LDS tile
+    // registers -> this wave's LDS tile; `fresh` (uniform): the window has not been stashed before, so with a finite
+    // tolerance its squares are added to the row norms (every chunk of X passes here exactly once)
+    auto stash_x = [&](const u32x4_t (&src)[TT][4], int slot, bool fresh) {
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) lds_x[slot * XSLOT + tt * 256 + i * 64 + lane] = src[tt][i];
+        if (want_norm && fresh) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float e[TR::kPerChunk];
+                    TR::unpack(src[tt][i], e);
+#pragma unroll
+                    for (int q = 0; q < TR::kPerChunk; ++q) nrm[tt][i] = fmaf(e[q], e[q], nrm[tt][i]);
+                }
+        }
     };
 
     load_c(0);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
     store_c(0);
-    stash_x(xr[0], 0);
+    stash_x(xr[0], 0, true);
     __syncthreads();
 
     const int nbody = (nss + UN - 1) / UN;
@@ -379,7 +434,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 if (stage + 1 < nstages) load_c(stage + 1);
             }
             load_x(xr[(p + D - 1) % D], gs + D - 1);
-            stash_x(xr[(p + 1) % D], (gs + 1) & 1);          // next super-step's tokens into the other slot
+            stash_x(xr[(p + 1) % D], (gs + 1) & 1, gs + 1 < nss);      // next super-step's tokens into the other slot
             if (gs < nss) {                                  // uniform; only false in the tail of the last body
                 const u32x4_t* cbuf = lds_c + buf * CBUF;
                 const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
@@ -507,15 +562,36 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
             best.merge(o);
         }
         const int row = row_base + 32 * tt + r;
+        // ||X_i||^2: row 8 i + L/8 of the fragment was loaded by the eight lanes L/8 = const, as their load i
+        float nx = 0.f;
+        if (want_norm) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float v = nrm[tt][i];
+                v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4);
+                const float w = __shfl(v, (r & 7) * 8);
+                nx = (i == (r >> 3)) ? w : nx;
+            }
+        }
+        const Neighbourhood nb{keep, &drop_count};
         if (FUSED) {
-            decide_or_queue(inv, cn2, hash, g == 0 && row < b, row, best, f, alpha, &redo_count, redo_entries);
+            decide_or_queue(inv, cn2, hash, g == 0 && row < b, row, best, nx, nb, f, alpha, &redo_count, redo_entries);
         } else {
-            if (g == 0 && row < b) best.store(cand + (size_t(row) * ncb + cb) * 2);
+            if (g == 0 && row < b) {
+                u32x4_t* rec = cand + (size_t(row) * ncb + cb) * 2;
+                best.store(rec);
+                Best::store_norm(rec, nx);
+            }
         }
     }
     if (FUSED) {
+        const Neighbourhood nb{keep, &drop_count};
         __syncthreads();
-        drain_queue<TR, NW>(X, C, cn2, nch, k, f, alpha, &redo_count, redo_entries);
+        drain_queue<TR, NW>(X, C, cn2, nch, k, nb, f, alpha, &redo_count, redo_entries);
+        if (want_norm) {
+            __syncthreads();
+            if (tid == 0 && drop_count > 0) atomicAdd(eta, drop_count);
+        }
     }
 }
 
@@ -526,7 +602,8 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
                                                   const float* __restrict__ inv, const double* __restrict__ cn2,
                                                   const unsigned long long* __restrict__ hash,
                                                   const u32x4_t* __restrict__ cand, int b, int nch, int k, int ncb,
-                                                  int32_t* __restrict__ f, float* __restrict__ alpha) {
+                                                  int32_t* __restrict__ f, float* __restrict__ alpha, double keep,
+                                                  int32_t* __restrict__ eta) {
     const int row = blockIdx.x * 256 + threadIdx.x;
     const bool valid = row < b;
     Best st;
@@ -538,13 +615,19 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
             if (cb == 0) st = o; else st.merge(o);
         }
     }
-    __shared__ int redo_count;
+    __shared__ int redo_count, drop_count;
     __shared__ int redo_entries[256 * kRedoInts];
-    if (threadIdx.x == 0) redo_count = 0;
+    if (threadIdx.x == 0) { redo_count = 0; drop_count = 0; }
     __syncthreads();
-    decide_or_queue(inv, cn2, hash, valid, row, st, f, alpha, &redo_count, redo_entries);
+    const Neighbourhood nb{keep, &drop_count};
+    const float nx = (valid && keep >= 0.0) ? Best::load_norm(cand + size_t(row) * ncb * 2) : 0.f;    // every block stores the same value
+    decide_or_queue(inv, cn2, hash, valid, row, st, nx, nb, f, alpha, &redo_count, redo_entries);
     __syncthreads();
-    drain_queue<TR, 4>(X, C, cn2, nch, k, f, alpha, &redo_count, redo_entries);
+    drain_queue<TR, 4>(X, C, cn2, nch, k, nb, f, alpha, &redo_count, redo_entries);
+    if (keep >= 0.0) {
+        __syncthreads();
+        if (threadIdx.x == 0 && drop_count > 0) atomicAdd(eta, drop_count);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------ host side
@@ -555,6 +638,7 @@ struct ScoreArgs {
     const void* X; const void* C; const float* inv; const double* cn2; const unsigned long long* hash;
     int b, nch, k;
     u32x4_t* cand; int32_t* f; float* alpha;
+    double keep; int32_t* eta;
 };
 
 template <typename TR, int TG, int TT, int NW, bool FUSED>
@@ -562,10 +646,10 @@ static void launch_score_cfg(const CompressPlan& pl, const ScoreArgs& a, hipStre
     dim3 grid((unsigned)(pl.row_tiles * pl.ncb));
     if (a.nch % 8 == 0)      // every row is a whole number of 128-byte super-steps
         hipLaunchKernelGGL((k_score<TR, TG, TT, NW, true, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
-                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha);
+                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
     else
         hipLaunchKernelGGL((k_score<TR, TG, TT, NW, false, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
-                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha);
+                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
 }
 
 template <typename TR, int TG, bool FUSED>
@@ -593,8 +677,8 @@ static void launch_score(const CompressPlan& pl, const ScoreArgs& a, hipStream_t
 }
 
 template <typename TR>
-static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, int n, int k, const int32_t* idx_src,
-                                void* C, int32_t* f, float* alpha, char* ws, hipStream_t s) {
+static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, int n, int k, const int32_t* idx_src, double keep,
+                                void* C, int32_t* f, float* alpha, int32_t* eta, char* ws, hipStream_t s) {
     const int nch = n / TR::kPerChunk;
     int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
     float* inv = reinterpret_cast<float*>(ws + pl.off_inv);
@@ -604,16 +688,16 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
 
     {
         ScopedSpan span(kGather, s);
-        hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_src, b, nch, (u32x4_t*)C, idx, inv, cn2, hash);
+        hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_src, b, nch, (u32x4_t*)C, idx, inv, cn2, hash, eta);
     }
     {
         ScopedSpan span(kScore, s);
-        launch_score<TR>(pl, ScoreArgs{X, C, inv, cn2, hash, b, nch, k, cand, f, alpha}, s);
+        launch_score<TR>(pl, ScoreArgs{X, C, inv, cn2, hash, b, nch, k, cand, f, alpha, keep, eta}, s);
     }
     if (pl.ncb > 1) {
         ScopedSpan span(kFinalize, s);
         hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv, cn2,
-                           hash, cand, b, nch, k, pl.ncb, f, alpha);
+                           hash, cand, b, nch, k, pl.ncb, f, alpha, keep, eta);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
@@ -647,19 +731,27 @@ static std::mutex g_ring_mu;
 
 using namespace pamm;
 
-extern "C" pamm_status pamm_compress_idx(const void* X, int64_t b, int64_t n, int64_t k, const int32_t* idx_dev, pamm_dtype dt,
-                                         void* C, int32_t* f, float* alpha, void* ws, size_t ws_bytes, void* stream) {
+// eps -> keep = 1 - eps^2 (negative: the condition cannot drop anything and is switched off)
+static pamm_status keep_of(float eps, double* keep) {
+    if (!(eps >= 0.f)) return PAMM_ERR_INVALID_ARG;          // negative or NaN
+    *keep = eps < 1.f ? 1.0 - double(eps) * double(eps) : -1.0;
+    return PAMM_OK;
+}
+
+static pamm_status compress_idx_impl(const void* X, int64_t b, int64_t n, int64_t k, const int32_t* idx_dev, double keep,
+                                     pamm_dtype dt, void* C, int32_t* f, float* alpha, int32_t* eta, void* ws, size_t ws_bytes,
+                                     void* stream) {
     CompressPlan pl;
     pamm_status st = check_compress_args(X, b, n, k, dt, C, f, alpha, ws, ws_bytes, &pl);
     if (st != PAMM_OK) return st;
     if (!idx_dev) return PAMM_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (dt == PAMM_BF16) return run_compress<Bf16>(pl, X, int(b), int(n), int(k), idx_dev, C, f, alpha, (char*)ws, s);
-    return run_compress<F32>(pl, X, int(b), int(n), int(k), idx_dev, C, f, alpha, (char*)ws, s);
+    if (dt == PAMM_BF16) return run_compress<Bf16>(pl, X, int(b), int(n), int(k), idx_dev, keep, C, f, alpha, eta, (char*)ws, s);
+    return run_compress<F32>(pl, X, int(b), int(n), int(k), idx_dev, keep, C, f, alpha, eta, (char*)ws, s);
 }
 
-extern "C" pamm_status pamm_compress(const void* X, int64_t b, int64_t n, int64_t k, uint64_t seed, pamm_dtype dt, void* C,
-                                     int32_t* f, float* alpha, void* ws, size_t ws_bytes, void* stream) {
+static pamm_status compress_seed_impl(const void* X, int64_t b, int64_t n, int64_t k, uint64_t seed, double keep, pamm_dtype dt,
+                                      void* C, int32_t* f, float* alpha, int32_t* eta, void* ws, size_t ws_bytes, void* stream) {
     CompressPlan pl;
     pamm_status st = check_compress_args(X, b, n, k, dt, C, f, alpha, ws, ws_bytes, &pl);
     if (st != PAMM_OK) return st;
@@ -691,9 +783,34 @@ extern "C" pamm_status pamm_compress(const void* X, int64_t b, int64_t n, int64_
     if (st != PAMM_OK) return st;
     const int32_t* didx = ring.dev + size_t(slot) * kMaxGenerators;
 
-    if (dt == PAMM_BF16) st = run_compress<Bf16>(pl, X, int(b), int(n), int(k), didx, C, f, alpha, (char*)ws, s);
-    else st = run_compress<F32>(pl, X, int(b), int(n), int(k), didx, C, f, alpha, (char*)ws, s);
+    if (dt == PAMM_BF16) st = run_compress<Bf16>(pl, X, int(b), int(n), int(k), didx, keep, C, f, alpha, eta, (char*)ws, s);
+    else st = run_compress<F32>(pl, X, int(b), int(n), int(k), didx, keep, C, f, alpha, eta, (char*)ws, s);
     if (hipEventRecord(ring.ev[slot], s) != hipSuccess) return PAMM_ERR_DEVICE;
     ring.used[slot] = true;
     return st;
+}
+
+extern "C" pamm_status pamm_compress_idx(const void* X, int64_t b, int64_t n, int64_t k, const int32_t* idx_dev, pamm_dtype dt,
+                                         void* C, int32_t* f, float* alpha, void* ws, size_t ws_bytes, void* stream) {
+    return compress_idx_impl(X, b, n, k, idx_dev, -1.0, dt, C, f, alpha, nullptr, ws, ws_bytes, stream);
+}
+
+extern "C" pamm_status pamm_compress(const void* X, int64_t b, int64_t n, int64_t k, uint64_t seed, pamm_dtype dt, void* C,
+                                     int32_t* f, float* alpha, void* ws, size_t ws_bytes, void* stream) {
+    return compress_seed_impl(X, b, n, k, seed, -1.0, dt, C, f, alpha, nullptr, ws, ws_bytes, stream);
+}
+
+extern "C" pamm_status pamm_compress_idx_eps(const void* X, int64_t b, int64_t n, int64_t k, const int32_t* idx_dev, float eps,
+                                             pamm_dtype dt, void* C, int32_t* f, float* alpha, int32_t* eta, void* ws,
+                                             size_t ws_bytes, void* stream) {
+    double keep;
+    if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
+    return compress_idx_impl(X, b, n, k, idx_dev, keep, dt, C, f, alpha, eta, ws, ws_bytes, stream);
+}
+
+extern "C" pamm_status pamm_compress_eps(const void* X, int64_t b, int64_t n, int64_t k, uint64_t seed, float eps, pamm_dtype dt,
+                                         void* C, int32_t* f, float* alpha, int32_t* eta, void* ws, size_t ws_bytes, void* stream) {
+    double keep;
+    if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
+    return compress_seed_impl(X, b, n, k, seed, keep, dt, C, f, alpha, eta, ws, ws_bytes, stream);
 }

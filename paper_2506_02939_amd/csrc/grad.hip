@@ -501,8 +501,16 @@ template <> struct PrepIo<F32> {
 template <typename TR>
 __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const float* __restrict__ partial,
                                               const int32_t* __restrict__ sbase, const int32_t* __restrict__ snum, int n, int m,
-                                              int k, int KC, int blocks_m, u32x4_t* __restrict__ Ct, u32x4_t* __restrict__ Bt) {
+                                              int k, int KC, int blocks_m, const int32_t* __restrict__ eta, int b,
+                                              u32x4_t* __restrict__ Ct, u32x4_t* __restrict__ Bt) {
     __shared__ float tile[64][17];
+    // normalisation factor of Sec. 3.2: beta = b / (b - eta) with eta rows dropped by the neighbourhood condition
+    // (1 without a tolerance; 0 if every row was dropped).  It scales Btilde, hence dW.
+    float beta = 1.f;
+    if (eta) {
+        const int dropped = *eta;
+        beta = dropped < b ? float(double(b) / double(b - dropped)) : 0.f;
+    }
     const int tid = threadIdx.x;
     const int j0 = blockIdx.y * 16;
     const bool is_b = int(blockIdx.x) < blocks_m;
@@ -524,6 +532,7 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
 #pragma unroll
                     for (int q = 0; q < 4; ++q) v += (t + q < np) ? p4[q] : 0.f;
                 }
+                v *= beta;
             } else {
                 v = PrepIo<TR>::load_c(C, size_t(j) * n + x);
             }
@@ -710,13 +719,14 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
 }
 
 template <typename TR>
-static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void* C, int n, int m, int k, float* dW, hipStream_t s) {
+static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void* C, int n, int m, int k, const int32_t* eta, int b,
+                            float* dW, hipStream_t s) {
     const int KC = int(pl.kpad) / TR::kPerChunk;
     const int blocks_m = (m + 63) / 64, blocks_n = (n + 63) / 64;
     {
         ScopedSpan span(kPrep, s);
         hipLaunchKernelGGL((k_prep<TR>), dim3((unsigned)(blocks_m + blocks_n), (unsigned)(pl.kpad / 16)), dim3(256), 0, s, C,
-                           g.partial, g.sbase, g.snum, n, m, k, KC, blocks_m, g.ct, g.bt);
+                           g.partial, g.sbase, g.snum, n, m, k, KC, blocks_m, eta, b, g.ct, g.bt);
     }
     const int tiles_n = (n + 127) / 128, tiles_m = (m + 127) / 128;
     const int per_xcd = (tiles_n * tiles_m + 7) / 8;
@@ -757,8 +767,8 @@ extern "C" pamm_status pamm_contract(const int32_t* f, const float* alpha, const
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
 
-extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t n,
-                                 int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws, size_t ws_bytes, void* stream) {
+static pamm_status grad_impl(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY, int64_t b,
+                             int64_t n, int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws, size_t ws_bytes, void* stream) {
     GradPlan pl;
     pamm_status st = plan_grad(b, n, k, m, dt, &pl);
     if (st != PAMM_OK) return st;
@@ -771,10 +781,22 @@ extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* a
     GradBuffers g = carve(pl, (char*)ws);
     if (dt == PAMM_BF16) {
         launch_group_contract<Bf16>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-        launch_prep_ctb<Bf16>(pl, g, C, int(n), int(m), int(k), dW, s);
+        launch_prep_ctb<Bf16>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, s);
     } else {
         launch_group_contract<F32>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-        launch_prep_ctb<F32>(pl, g, C, int(n), int(m), int(k), dW, s);
+        launch_prep_ctb<F32>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, s);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
+}
+
+extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t n,
+                                 int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws, size_t ws_bytes, void* stream) {
+    return grad_impl(C, f, alpha, nullptr, dY, b, n, k, m, dt, dW, ws, ws_bytes, stream);
+}
+
+extern "C" pamm_status pamm_grad_eps(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY,
+                                     int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws,
+                                     size_t ws_bytes, void* stream) {
+    if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u)) return PAMM_ERR_INVALID_ARG;
+    return grad_impl(C, f, alpha, eta, dY, b, n, k, m, dt, dW, ws, ws_bytes, stream);
 }

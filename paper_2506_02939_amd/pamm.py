@@ -21,7 +21,8 @@ PAMM_F32, PAMM_BF16 = 0, 1
 
 EXPORTS = [
     "pamm_status_string", "pamm_compress_workspace", "pamm_grad_workspace", "pamm_sample_indices",
-    "pamm_compress", "pamm_compress_idx", "pamm_grad", "pamm_contract",
+    "pamm_compress", "pamm_compress_idx", "pamm_compress_eps", "pamm_compress_idx_eps", "pamm_grad", "pamm_grad_eps",
+    "pamm_contract",
     "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
 ]
 NUM_KERNELS = 8
@@ -52,8 +53,14 @@ def _load() -> ctypes.CDLL:
     lib.pamm_compress.restype = ci
     lib.pamm_compress_idx.argtypes = [vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, sz, vp]
     lib.pamm_compress_idx.restype = ci
+    lib.pamm_compress_eps.argtypes = [vp, i64, i64, i64, u64, ctypes.c_float, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pamm_compress_eps.restype = ci
+    lib.pamm_compress_idx_eps.argtypes = [vp, i64, i64, i64, vp, ctypes.c_float, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pamm_compress_idx_eps.restype = ci
     lib.pamm_grad.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_grad.restype = ci
+    lib.pamm_grad_eps.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, sz, vp]
+    lib.pamm_grad_eps.restype = ci
     lib.pamm_contract.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_contract.restype = ci
     lib.pamm_profile_begin.argtypes = []
@@ -123,11 +130,13 @@ class Compressed:
     C: torch.Tensor       # k x n, element type of X
     f: torch.Tensor       # b int32
     alpha: torch.Tensor   # b fp32
+    eta: torch.Tensor | None = None     # one int32 on the device: rows dropped by the neighbourhood condition (eps given)
 
 
-def compress(X: torch.Tensor, k: int, seed: int = 0, *, idx: torch.Tensor | None = None, out: Compressed | None = None,
-             ws: torch.Tensor | None = None) -> Compressed:
-    """pamm_compress (or pamm_compress_idx when `idx`, a device int32 tensor of k rows, is given)."""
+def compress(X: torch.Tensor, k: int, seed: int = 0, *, idx: torch.Tensor | None = None, eps: float | None = None,
+             out: Compressed | None = None, ws: torch.Tensor | None = None) -> Compressed:
+    """pamm_compress (or pamm_compress_idx when `idx`, a device int32 tensor of k rows, is given); with `eps` the
+    _eps forms, which also fill `eta`."""
     b, n = X.shape
     dt = _dtype_code(X)
     xp = _dev(X, "X")
@@ -141,7 +150,20 @@ def compress(X: torch.Tensor, k: int, seed: int = 0, *, idx: torch.Tensor | None
         ws = _workspace(16, X.device, ws)
     else:
         ws = _workspace(nbytes, X.device, ws)
-    if idx is None:
+    if eps is not None:
+        if out.eta is None:
+            out.eta = torch.empty(1, dtype=torch.int32, device=X.device)
+        if idx is None:
+            st = lib.pamm_compress_eps(xp, b, n, k, ctypes.c_uint64(seed & (2**64 - 1)), ctypes.c_float(eps), dt, out.C.data_ptr(),
+                                       out.f.data_ptr(), out.alpha.data_ptr(), out.eta.data_ptr(), ws.data_ptr(), ws.numel(),
+                                       _stream())
+            _check(st, "pamm_compress_eps")
+        else:
+            st = lib.pamm_compress_idx_eps(xp, b, n, k, _dev(idx, "idx"), ctypes.c_float(eps), dt, out.C.data_ptr(),
+                                           out.f.data_ptr(), out.alpha.data_ptr(), out.eta.data_ptr(), ws.data_ptr(), ws.numel(),
+                                           _stream())
+            _check(st, "pamm_compress_idx_eps")
+    elif idx is None:
         st = lib.pamm_compress(xp, b, n, k, ctypes.c_uint64(seed & (2**64 - 1)), dt, out.C.data_ptr(), out.f.data_ptr(),
                                out.alpha.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
         _check(st, "pamm_compress")
@@ -152,9 +174,9 @@ def compress(X: torch.Tensor, k: int, seed: int = 0, *, idx: torch.Tensor | None
     return out
 
 
-def grad(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, *, out: torch.Tensor | None = None,
-         ws: torch.Tensor | None = None) -> torch.Tensor:
-    """pamm_grad: dW (n x m, fp32) = C^T Btilde."""
+def grad(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, *, eta: torch.Tensor | None = None,
+         out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """pamm_grad: dW (n x m, fp32) = C^T Btilde; with `eta` (device int32) pamm_grad_eps: beta C^T Btilde."""
     k, n = C.shape
     b, m = dY.shape
     dt = _dtype_code(dY)
@@ -163,9 +185,14 @@ def grad(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor
     if out is None:
         out = torch.empty(n, m, dtype=torch.float32, device=dY.device)
     ws = _workspace(grad_workspace(b, n, k, m, dt), dY.device, ws)
-    st = lib.pamm_grad(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, dt, out.data_ptr(),
-                       ws.data_ptr(), ws.numel(), _stream())
-    _check(st, "pamm_grad")
+    if eta is None:
+        st = lib.pamm_grad(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, dt, out.data_ptr(),
+                           ws.data_ptr(), ws.numel(), _stream())
+        _check(st, "pamm_grad")
+    else:
+        st = lib.pamm_grad_eps(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(eta, "eta"), _dev(dY, "dY"), b, n, k, m, dt,
+                               out.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+        _check(st, "pamm_grad_eps")
     return out
 
 

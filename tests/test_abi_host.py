@@ -127,6 +127,37 @@ def test_grad_argument_checks(pamm):
     assert _contract(P, k=0) == P.PAMM_ERR_INVALID_ARG
 
 
+def _compress_eps(pamm, X=A, b=64, n=64, k=4, seed=0, eps=0.5, dt=1, C=A, f=A, alpha=A, eta=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_compress_eps(X, b, n, k, ctypes.c_uint64(seed), ctypes.c_float(eps), dt, C, f, alpha, eta, ws, ws_bytes, None)
+
+
+def _compress_idx_eps(pamm, X=A, b=64, n=64, k=4, idx=A, eps=0.5, dt=1, C=A, f=A, alpha=A, eta=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_compress_idx_eps(X, b, n, k, idx, ctypes.c_float(eps), dt, C, f, alpha, eta, ws, ws_bytes, None)
+
+
+def _grad_eps(pamm, C=A, f=A, alpha=A, eta=A, dY=A, b=64, n=64, k=4, m=64, dt=1, dW=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_grad_eps(C, f, alpha, eta, dY, b, n, k, m, dt, dW, ws, ws_bytes, None)
+
+
+def test_tolerance_argument_checks(pamm):
+    """The eps forms refuse a negative or NaN tolerance and a missing or misaligned eta before anything else."""
+    P = pamm
+    for fn in (_compress_eps, _compress_idx_eps):
+        assert fn(P, eps=-0.1) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, eps=float("nan")) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, eta=None) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, eta=A + 2) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, X=None) == P.PAMM_ERR_INVALID_ARG
+        assert fn(P, n=60) == P.PAMM_ERR_UNSUPPORTED
+        assert fn(P, ws_bytes=16) == P.PAMM_ERR_WORKSPACE
+        assert fn(P, eps=float("inf"), ws=None) == P.PAMM_ERR_WORKSPACE        # an infinite tolerance is legal
+    assert _compress_idx_eps(P, idx=None) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_eps(P, eta=None) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_eps(P, eta=A + 1) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_eps(P, dW=None) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_eps(P, ws_bytes=1024) == P.PAMM_ERR_WORKSPACE
+
+
 def test_binding_refuses_cpu_tensors(pamm):
     import torch
 
