@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=2,
                     help="copies of (X, dY) in HBM that consecutive steps rotate through, so that no input survives in the "
                          "256 MiB Infinity Cache from one step to the next (1 = every step re-reads the same buffers)")
+    ap.add_argument("--eps", type=float, default=None,
+                    help="time the path with the neighbourhood condition of Eq. 2 at this tolerance (default: none, eps = infinity)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -88,8 +90,8 @@ def main() -> int:
     ws_g = torch.empty(pamm.grad_workspace(b, n, k, m, dt), dtype=torch.uint8, device="cuda")
 
     def step(i):
-        pamm.compress(Xs[i % nsets], k, seed=i, out=out, ws=ws_c)      # fresh generators every step, as in training (App. F)
-        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], out=dW, ws=ws_g)
+        pamm.compress(Xs[i % nsets], k, seed=i, eps=args.eps, out=out, ws=ws_c)      # fresh generators every step, as in training (App. F)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g)
 
     for i in range(args.warmup):
         step(i)
@@ -107,9 +109,9 @@ def main() -> int:
     reps = max(1, min(args.steps, 50))
     for i in range(reps):
         ev[0].record()
-        pamm.compress(Xs[i % nsets], k, seed=i, out=out, ws=ws_c)
+        pamm.compress(Xs[i % nsets], k, seed=i, eps=args.eps, out=out, ws=ws_c)
         ev[1].record()
-        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], out=dW, ws=ws_g)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g)
         ev[2].record()
         torch.cuda.synchronize()
         tc += ev[0].elapsed_time(ev[1])
@@ -152,7 +154,7 @@ def main() -> int:
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "b": b, "n": n, "m": m, "k": k, "dtype": w.dtype,
                    "recipe": f"{w.centres} centres, sigma {w.sigma}, {w.structure}, pad {w.pad_frac}",
-                   "input_sets_rotated": nsets},
+                   "input_sets_rotated": nsets, "eps": args.eps},
         "ms_compress": round(tc, 4), "ms_grad": round(tg, 4),
         "roofline": roofline,
         "kernels": kernels,
@@ -189,9 +191,9 @@ def main() -> int:
         reps_cpu = 3
         for _ in range(reps_cpu):
             c0 = time.perf_counter()
-            oc = pamm_oracle.compress(X_cpu, k, seed=0)
+            oc = pamm_oracle.compress(X_cpu, k, seed=0, eps=float("inf") if args.eps is None else args.eps)
             c1 = time.perf_counter()
-            pamm_oracle.grad(oc.C, oc.f, oc.alpha, dY_cpu)
+            pamm_oracle.grad(oc.C, oc.f, oc.alpha, dY_cpu, beta=oc.beta)
             c2 = time.perf_counter()
             if best is None or c2 - c0 < best[0]:
                 best = (c2 - c0, c1 - c0, c2 - c1)
