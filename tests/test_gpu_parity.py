@@ -246,6 +246,45 @@ def test_grad_clamps_out_of_range_assignments(pamm):
     assert torch.equal(a, c)
 
 
+def test_step_can_be_captured_in_a_hip_graph(pamm):
+    """pamm_compress_idx + pamm_grad allocate nothing, never synchronise and record no memset, so a caller can capture
+    them.  Every replay (with eager work and synchronisations in between) must give the eager result bit for bit."""
+    w = workloads.scaled(workloads.WORKLOADS["llama60m"], name="graph", seqs=4, seq_len=300, n=256, m=776, k=24, centres=40)
+    X, dY = workloads.generate(w)
+    X, dY = X.cuda(), dY.cuda()
+    b, n, m, k = w.b, w.n, w.m, w.k
+    out = pamm.Compressed(torch.empty(k, n, dtype=X.dtype, device="cuda"), torch.empty(b, dtype=torch.int32, device="cuda"),
+                          torch.empty(b, dtype=torch.float32, device="cuda"))
+    dW = torch.empty(n, m, dtype=torch.float32, device="cuda")
+    ws_c = torch.empty(pamm.compress_workspace(b, n, k, pamm.PAMM_BF16), dtype=torch.uint8, device="cuda")
+    ws_g = torch.empty(pamm.grad_workspace(b, n, k, m, pamm.PAMM_BF16), dtype=torch.uint8, device="cuda")
+    idx = pamm.sample_indices(b, k, 5).cuda()
+
+    def step():
+        pamm.compress(X, k, idx=idx, out=out, ws=ws_c)
+        pamm.grad(out.C, out.f, out.alpha, dY, out=dW, ws=ws_g)
+
+    step()
+    torch.cuda.synchronize()
+    ref_dw, ref_f, ref_a = dW.clone(), out.f.clone(), out.alpha.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for _ in range(4):
+        dW.zero_(); out.f.zero_(); out.alpha.zero_()
+        junk = torch.randn(1 << 20, device="cuda").sum().item()       # eager work and a synchronisation between replays
+        assert junk == junk
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dW, ref_dw) and torch.equal(out.f, ref_f) and torch.equal(out.alpha, ref_a)
+
+
 # ---------------------------------------------------------------------------- the BASELINE configurations, full size
 
 FULL = ["tiny", "llama60m", "llama350m", "llama1b", "llama7b_k32", "llama7b_k256", "llama7b_k1024"]
