@@ -127,6 +127,11 @@ SMALL = [
     ("bf16_k2500_per_generator_grouping", "llama1b", dict(seqs=3, seq_len=1000, n=32, m=40, k=2500, centres=3000)),
     # b > 65536 together with k > 2048: the grouping kernel that streams f twice
     ("bf16_many_rows_many_generators", "llama1b", dict(seqs=6, seq_len=11003, n=8, m=8, k=2100, centres=2500)),
+    # 1.5 M rows: chunks of the sorted list at their largest size, long slices in the counting sort, > 4096 row tiles
+    ("bf16_1500k_rows", "llama60m", dict(seqs=3, seq_len=500001, n=16, m=16, k=8, centres=12)),
+    # long rows: 256 windows of the hidden dimension per row in k_score, 33 column groups in k_contract
+    ("bf16_long_rows", "llama7b_k32", dict(seqs=1, seq_len=300, n=16384, m=16392, k=5, centres=8)),
+    ("f32_long_rows", "tiny", dict(seqs=1, seq_len=130, n=8196, m=4100, k=3, centres=5)),
 ]
 
 
