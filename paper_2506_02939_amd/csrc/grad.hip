@@ -555,9 +555,9 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
 // ------------------------------------------------------------------------------------------------
 // k_ctb: dW (n x m) = C^T (n x k) * Btilde (k x m).  Both operands come from k_prep with the generator index
 // contiguous (Ct[l][j], Bt[c][j]).  Workgroup tile 128 x 128, 4 waves of 64 x 64; the generator index is walked in
-// stages of BK chunks per row (8: 64 bf16 / 32 fp32; 4 when there are few generators, which halves the LDS of a
-// workgroup so that three of them fit a CU and the whole grid is resident at once), staged through LDS with
-// coalesced loads, double buffered, one barrier per stage.  LDS rows are BK+1 chunks apart, which makes the
+// stages of BK = 4 chunks per row (32 bf16 / 16 fp32: 40 KiB of LDS per workgroup, so three workgroups share a CU;
+// the kernel is bound by latencies, not by LDS or MFMA throughput, and eight-chunk stages with two workgroups per
+// CU measured 13 % slower at k = 1024), staged through LDS with coalesced loads, double buffered, one barrier per stage.  LDS rows are BK+1 chunks apart, which makes the
 // 16-byte reads of a fragment (32 rows, one chunk column) free of bank conflicts.  MFMA step u of a stage takes
 // chunk 2u+g from lane group g, for both operands alike.
 //
@@ -732,12 +732,8 @@ static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void
     const int per_xcd = (tiles_n * tiles_m + 7) / 8;
     {
         ScopedSpan span(kCtb, s);
-        if (KC <= 32)     // up to 256 bf16 / 128 fp32 generators: short stages, three workgroups per CU
-            hipLaunchKernelGGL((k_ctb<TR, 4>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_n,
-                               tiles_m, per_xcd, dW);
-        else
-            hipLaunchKernelGGL((k_ctb<TR, 8>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_n,
-                               tiles_m, per_xcd, dW);
+        hipLaunchKernelGGL((k_ctb<TR, 4>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_n, tiles_m,
+                           per_xcd, dW);
     }
 }
 
