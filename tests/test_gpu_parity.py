@@ -1,6 +1,6 @@
 """GPU parity: libpamm (HIP, through the C ABI) against the fp64 CPU oracle, element by element, same seeded inputs.
 
-Bars (BASELINE the benchmark spec): f bit-exact except rows whose two best oracle scores differ by < 1e-6 relative;
+Bars: f bit-exact except rows whose two best oracle scores differ by < 1e-6 relative;
 alpha, C, dW within relative Frobenius error 1e-4 (fp32 inputs) / 2e-2 (bf16 inputs).  Tighter engineering bars
 derived from the arithmetic are asserted as well: C is a bit copy; alpha and Btilde come from fp32 accumulation of
 exactly representable products (<= 2e-5); for bf16 inputs dW carries one bf16 rounding of Btilde (<= 2^-8).
@@ -290,7 +290,7 @@ def test_step_can_be_captured_in_a_hip_graph(pamm):
         assert torch.equal(dW, ref_dw) and torch.equal(out.f, ref_f) and torch.equal(out.alpha, ref_a)
 
 
-# ---------------------------------------------------------------------------- the BASELINE configurations, full size
+# ---------------------------------------------------------------------------- the five benchmark configurations, full size
 
 FULL = ["tiny", "llama60m", "llama350m", "llama1b", "llama7b_k32", "llama7b_k256", "llama7b_k1024"]
 
