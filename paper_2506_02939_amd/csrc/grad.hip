@@ -20,41 +20,64 @@ namespace pamm {
 // L2): pass 1 counts rows with key < j (start of generator j's list) and key == j per wave, pass 2
 // compacts the matching row numbers with ballots, which keeps them in increasing order.
 //
-// The sorted list holds one 16-byte entry per row: {row number, alpha_i (bits), generator, 0}.  It is later
-// cut into chunks of P consecutive positions; a
-// "piece" is a maximal run of one generator inside one chunk and is numbered chunk + generator.
-// Piece numbers are unique, increase along the list and stay below ceil(b/P) + k.  Generator j owns
-// the pieces [seg_start_j / P + j, (seg_end_j - 1) / P + j].
-__device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, int i0, int b, int k, int (&key)[4]) {
+// The sorted list holds one 16-byte entry per row with a non-zero weight: {row number, alpha_i (bits), generator, 0}.
+// Rows with alpha_i = 0 (dropped by the neighbourhood condition, or orthogonal to their generator) add nothing to
+// Btilde and are left out, so their rows of dY are never read.  The list of L entries is later cut into chunks of P
+// consecutive positions, P chosen on the device from L so that every CU gets one chunk; a "piece" is a maximal
+// run of one generator inside one chunk and is numbered chunk + generator.  Piece numbers are unique, increase
+// along the list and stay below the number of chunks + k.  Generator j owns the pieces
+// [seg_start_j / P + j, (seg_end_j - 1) / P + j].
+__device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, const float* __restrict__ alpha, int i0, int b, int k,
+                                          int (&key)[4]) {
+    float w[4];
     if (i0 + 3 < b) {
-        int4 v = *reinterpret_cast<const int4*>(f + i0);
+        const int4 v = *reinterpret_cast<const int4*>(f + i0);
+        const float4 a = *reinterpret_cast<const float4*>(alpha + i0);
         key[0] = v.x; key[1] = v.y; key[2] = v.z; key[3] = v.w;
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
     } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) key[c] = (i0 + c < b) ? f[i0 + c] : -1;
+        for (int c = 0; c < 4; ++c) {
+            key[c] = (i0 + c < b) ? f[i0 + c] : -1;
+            w[c] = (i0 + c < b) ? alpha[i0 + c] : 0.f;
+        }
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        bool in = i0 + c < b;
+        const bool in = i0 + c < b && w[c] != 0.f;
         int v = key[c];
         v = v < 0 ? 0 : (v >= k ? k - 1 : v);
         key[c] = in ? v : k;            // k = "no row": larger than every generator number
     }
 }
 
+// What the grouping kernels leave for k_contract: hdr[0] = L, entries in the list; hdr[1] = P, positions per chunk.
+constexpr int kHdrInts = 4;
+
+// Chunk size for a list of L entries: one chunk per CU and workgroup column (256 CUs), a multiple of 16, at most 4096;
+// p_fixed > 0 overrides (tuning).  The host sizes the partial-row buffer for the largest chunk count this can give.
+__device__ __forceinline__ int piece_rows_for(int L, int wg_cols, int p_fixed) {
+    if (p_fixed > 0) return p_fixed;
+    long long P = ((long long)L * wg_cols + 255) / 256;
+    P = (P + 15) / 16 * 16;
+    return int(P < 16 ? 16 : (P > 4096 ? 4096 : P));
+}
+
 __device__ __forceinline__ u32x4_t list_entry(int row, float a, int key) {
     return u32x4_t{uint32_t(row), __float_as_uint(a), uint32_t(key), 0u};
 }
 
-// Entries b .. roundup(b,16)-1 of the sorted list: a valid row, weight 0, the key of the last real entry.
-__device__ __forceinline__ void pad_list(u32x4_t* __restrict__ list, int b, int last_key) {
-    for (int q = b; q < (b + 15) / 16 * 16; ++q) list[q] = list_entry(0, 0.f, last_key);
+// Entries L .. roundup(L,16)-1 of the sorted list repeat the last real entry with weight 0 (a row that is read
+// anyway, so the padding touches no other row of dY).  Written by whoever writes entry L-1.
+__device__ __forceinline__ void pad_list(u32x4_t* __restrict__ list, int L, int last_row, int last_key) {
+    for (int q = L; q < (L + 15) / 16 * 16; ++q) list[q] = list_entry(last_row, 0.f, last_key);
 }
 
 // Generic version: two passes over f from L2, any b.
 __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                       int P, u32x4_t* __restrict__ list, int32_t* __restrict__ sbase,
-                                                       int32_t* __restrict__ snum) {
+                                                       int wg_cols, int p_fixed, u32x4_t* __restrict__ list,
+                                                       int32_t* __restrict__ sbase, int32_t* __restrict__ snum,
+                                                       int32_t* __restrict__ hdr) {
     const int j = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const long long per_wave = (((long long)b + 15) / 16 + 255) / 256 * 256;
@@ -62,25 +85,28 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
     const int r0 = r0l < b ? int(r0l) : b;
     const int r1 = (r0l + per_wave) < b ? int(r0l + per_wave) : b;
 
-    int lt = 0, eq = 0;
+    int lt = 0, eq = 0, live = 0;
     for (int base = r0; base < r1; base += 256) {
         int key[4];
-        load_keys(f, base + 4 * lane, b, k, key);
+        load_keys(f, alpha, base + 4 * lane, b, k, key);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) { lt += key[c] < j; eq += key[c] == j; }
+        for (int c = 0; c < 4; ++c) { lt += key[c] < j; eq += key[c] == j; live += key[c] < k; }
     }
     lt = wave_sum(lt);
     eq = wave_sum(eq);
-    __shared__ int s_lt[16], s_eq[16];
-    if (lane == 0) { s_lt[wave] = lt; s_eq[wave] = eq; }
+    live = wave_sum(live);
+    __shared__ int s_lt[16], s_eq[16], s_live[16];
+    if (lane == 0) { s_lt[wave] = lt; s_eq[wave] = eq; s_live[wave] = live; }
     __syncthreads();
-    int seg_start = 0, count = 0, woff = 0;
+    int seg_start = 0, count = 0, woff = 0, L = 0;
 #pragma unroll
     for (int w = 0; w < 16; ++w) {
         seg_start += s_lt[w];
         woff += (w < wave) ? s_eq[w] : 0;
         count += s_eq[w];
+        L += s_live[w];
     }
+    const int P = piece_rows_for(L, wg_cols, p_fixed);
 
     if (s_eq[wave] > 0) {                  // wave-uniform: most waves hold no row of this generator when k is large
         int pos = seg_start + woff;
@@ -88,7 +114,7 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
         for (int base = r0; base < r1; base += 256) {
             const int i0 = base + 4 * lane;
             int key[4];
-            load_keys(f, i0, b, k, key);
+            load_keys(f, alpha, i0, b, k, key);
             int before = 0, total = 0;
             bool hit[4];
 #pragma unroll
@@ -103,6 +129,7 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
             for (int c = 0; c < 4; ++c) {
                 if (hit[c]) {
                     list[pos + before + within] = list_entry(i0 + c, alpha[i0 + c], j);
+                    if (pos + before + within == L - 1) pad_list(list, L, i0 + c, j);
                     ++within;
                 }
             }
@@ -112,7 +139,7 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
     if (tid == 0) {
         sbase[j] = seg_start / P + j;
         snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
-        if (count > 0 && seg_start + count == b) pad_list(list, b, j);
+        if (j == 0) { hdr[0] = L; hdr[1] = P; }
     }
 }
 
@@ -120,32 +147,36 @@ __global__ __launch_bounds__(1024) void k_group_stream(const int32_t* __restrict
 // registers, so f is read once and both passes run out of registers.
 template <int NV>
 __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                     int P, u32x4_t* __restrict__ list, int32_t* __restrict__ sbase,
-                                                     int32_t* __restrict__ snum) {
+                                                     int wg_cols, int p_fixed, u32x4_t* __restrict__ list,
+                                                     int32_t* __restrict__ sbase, int32_t* __restrict__ snum,
+                                                     int32_t* __restrict__ hdr) {
     const int j = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r0 = wave * (NV * 256);
     int key[NV][4];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) load_keys(f, r0 + v * 256 + 4 * lane, b, k, key[v]);
+    for (int v = 0; v < NV; ++v) load_keys(f, alpha, r0 + v * 256 + 4 * lane, b, k, key[v]);
 
-    int lt = 0, eq = 0;
+    int lt = 0, eq = 0, live = 0;
 #pragma unroll
     for (int v = 0; v < NV; ++v)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) { lt += key[v][c] < j; eq += key[v][c] == j; }
+        for (int c = 0; c < 4; ++c) { lt += key[v][c] < j; eq += key[v][c] == j; live += key[v][c] < k; }
     lt = wave_sum(lt);
     eq = wave_sum(eq);
-    __shared__ int s_lt[16], s_eq[16];
-    if (lane == 0) { s_lt[wave] = lt; s_eq[wave] = eq; }
+    live = wave_sum(live);
+    __shared__ int s_lt[16], s_eq[16], s_live[16];
+    if (lane == 0) { s_lt[wave] = lt; s_eq[wave] = eq; s_live[wave] = live; }
     __syncthreads();
-    int seg_start = 0, count = 0, woff = 0;
+    int seg_start = 0, count = 0, woff = 0, L = 0;
 #pragma unroll
     for (int w = 0; w < 16; ++w) {
         seg_start += s_lt[w];
         woff += (w < wave) ? s_eq[w] : 0;
         count += s_eq[w];
+        L += s_live[w];
     }
+    const int P = piece_rows_for(L, wg_cols, p_fixed);
 
     if (eq > 0) {                          // wave-uniform
         int pos = seg_start + woff;
@@ -168,6 +199,7 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
                 for (int c = 0; c < 4; ++c) {
                     if (hit[c]) {
                         list[pos + before + within] = list_entry(i0 + c, alpha[i0 + c], j);
+                        if (pos + before + within == L - 1) pad_list(list, L, i0 + c, j);
                         ++within;
                     }
                 }
@@ -178,7 +210,7 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
     if (tid == 0) {
         sbase[j] = seg_start / P + j;
         snum[j] = count > 0 ? (seg_start + count - 1) / P - seg_start / P + 1 : 0;
-        if (count > 0 && seg_start + count == b) pad_list(list, b, j);
+        if (j == 0) { hdr[0] = L; hdr[1] = P; }
     }
 }
 
@@ -193,11 +225,12 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
 constexpr int kScatterMaxK = 2048;     // (NT/64 + 2) * k ints of LDS
 
 template <int NT>
-__global__ __launch_bounds__(NT) void k_hist(const int32_t* __restrict__ f, int b, int k, int32_t* __restrict__ table) {
+__global__ __launch_bounds__(NT) void k_hist(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
+                                             int32_t* __restrict__ table) {
     extern __shared__ int hist[];
     const int tid = threadIdx.x;
     int key[4];
-    load_keys(f, blockIdx.x * (4 * NT) + 4 * tid, b, k, key);
+    load_keys(f, alpha, blockIdx.x * (4 * NT) + 4 * tid, b, k, key);
     for (int j = tid; j < k; j += NT) hist[j] = 0;
     __syncthreads();
 #pragma unroll
@@ -209,9 +242,9 @@ __global__ __launch_bounds__(NT) void k_hist(const int32_t* __restrict__ f, int 
 
 template <int NT>
 __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
-                                                int P, int nslices, const int32_t* __restrict__ table,
+                                                int wg_cols, int p_fixed, int nslices, const int32_t* __restrict__ table,
                                                 u32x4_t* __restrict__ list, int32_t* __restrict__ sbase,
-                                                int32_t* __restrict__ snum) {
+                                                int32_t* __restrict__ snum, int32_t* __restrict__ hdr) {
     constexpr int NWV = NT / 64;
     extern __shared__ int lds[];
     int* wh = lds;                 // [NWV][k] per-wave counts, later per-wave next free position inside the generator's list
@@ -225,7 +258,7 @@ __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, c
     // kernel pays one memory latency, not one per phase
     int key[4];
     const int i0 = slice * (4 * NT) + 4 * tid;        // wave w owns rows [256 w, 256 w + 256) of the slice
-    load_keys(f, i0, b, k, key);
+    load_keys(f, alpha, i0, b, k, key);
     float al[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) al[c] = alpha[min(i0 + c, b - 1)];
@@ -298,14 +331,20 @@ __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, c
         const int start = carry + wpre + incl - x;
         if (j < k) {
             tot[j] = start;
-            if (slice == 0) {
-                sbase[j] = start / P + j;
-                snum[j] = x > 0 ? (start + x - 1) / P - start / P + 1 : 0;
-                if (x > 0 && start + x == b) pad_list(list, b, j);      // j owns the end of the list
-            }
+            bef[j] = x;                         // bef is free by now: keep the generator's row count for the tail below
         }
         carry += all;
         __syncthreads();
+    }
+    const int L = carry;                        // the list's length is known now
+    if (slice == 0) {                           // chunk size, pieces per generator
+        const int P = piece_rows_for(L, wg_cols, p_fixed);
+        for (int j = tid; j < k; j += NT) {
+            const int start = tot[j], x = bef[j];
+            sbase[j] = start / P + j;
+            snum[j] = x > 0 ? (start + x - 1) / P - start / P + 1 : 0;
+        }
+        if (tid == 0) { hdr[0] = L; hdr[1] = P; }
     }
 
 #pragma unroll
@@ -313,6 +352,7 @@ __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, c
         if (key[c] < k) {
             const int pos = tot[key[c]] + atomicAdd(&wh[wave * k + key[c]], 1);
             list[pos] = list_entry(i0 + c, al[c], key[c]);
+            if (pos == L - 1) pad_list(list, L, i0 + c, key[c]);
         }
     }
 }
@@ -358,14 +398,17 @@ template <> struct RowLoad<F32> {       // 8 columns = two 16-byte chunks
 // Workgroup = 4 waves that share a chunk of the list and sit side by side along the row: wave w covers W
 // consecutive 512-column groups, so the workgroup reads 4*W KiB of every row at (nearly) the same time.
 template <typename TR, int W>
-__global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const u32x4_t* __restrict__ list, int b,
-                                                  int P, int mch, int m, int wgcols, float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY, const u32x4_t* __restrict__ list,
+                                                  const int32_t* __restrict__ hdr, int mch, int m, int wgcols,
+                                                  float* __restrict__ partial) {
     const int chunk = blockIdx.x / wgcols, wc = blockIdx.x % wgcols;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int grp0 = (wc * 4 + wave) * W;
     if (grp0 * 512 >= m) return;                           // this wave has no columns (uniform per wave)
+    const int L = __builtin_amdgcn_readfirstlane(hdr[0]), P = __builtin_amdgcn_readfirstlane(hdr[1]);
     const int s0 = chunk * P;
-    const int s1 = min(b, s0 + P);
+    if (s0 >= L) return;                                   // the list ends before this chunk (uniform per workgroup)
+    const int s1 = min(L, s0 + P);
     int ch[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) ch[w] = RowLoad<TR>::chunk_of(grp0 + w, lane, mch);
@@ -658,7 +701,7 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct GradBuffers {
-    int32_t *sbase, *snum, *table;
+    int32_t *sbase, *snum, *table, *hdr;
     float* partial;
     u32x4_t *list, *ct, *bt;
 };
@@ -669,6 +712,7 @@ static GradBuffers carve(const GradPlan& pl, char* ws) {
     g.sbase = reinterpret_cast<int32_t*>(ws + pl.off_sbase);
     g.snum = reinterpret_cast<int32_t*>(ws + pl.off_snum);
     g.table = reinterpret_cast<int32_t*>(ws + pl.off_table);
+    g.hdr = reinterpret_cast<int32_t*>(ws + pl.off_hdr);
     g.partial = reinterpret_cast<float*>(ws + pl.off_partial);
     g.ct = reinterpret_cast<u32x4_t*>(ws + pl.off_ct);
     g.bt = reinterpret_cast<u32x4_t*>(ws + pl.off_bt);
@@ -683,17 +727,17 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
         if (k <= kScatterMaxK) {
             const int nslices = int(pl.nslices);
             if (pl.slice_rows == 1024) {
-                hipLaunchKernelGGL(k_hist<256>, dim3(nslices), dim3(256), size_t(k) * 4, s, f, b, k, g.table);
-                hipLaunchKernelGGL(k_scatter<256>, dim3(nslices), dim3(256), size_t(4 + 2) * k * 4, s, f, alpha, b, k, pl.piece_rows,
-                                   nslices, g.table, g.list, g.sbase, g.snum);
+                hipLaunchKernelGGL(k_hist<256>, dim3(nslices), dim3(256), size_t(k) * 4, s, f, alpha, b, k, g.table);
+                hipLaunchKernelGGL(k_scatter<256>, dim3(nslices), dim3(256), size_t(4 + 2) * k * 4, s, f, alpha, b, k, pl.wg_cols,
+                                   pl.p_fixed, nslices, g.table, g.list, g.sbase, g.snum, g.hdr);
             } else {
-                hipLaunchKernelGGL(k_hist<1024>, dim3(nslices), dim3(1024), size_t(k) * 4, s, f, b, k, g.table);
+                hipLaunchKernelGGL(k_hist<1024>, dim3(nslices), dim3(1024), size_t(k) * 4, s, f, alpha, b, k, g.table);
                 hipLaunchKernelGGL(k_scatter<1024>, dim3(nslices), dim3(1024), size_t(16 + 2) * k * 4, s, f, alpha, b, k,
-                                   pl.piece_rows, nslices, g.table, g.list, g.sbase, g.snum);
+                                   pl.wg_cols, pl.p_fixed, nslices, g.table, g.list, g.sbase, g.snum, g.hdr);
             }
         } else {
 #define PAMM_LAUNCH_GROUP(KERNEL) \
-    hipLaunchKernelGGL(KERNEL, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.piece_rows, g.list, g.sbase, g.snum)
+    hipLaunchKernelGGL(KERNEL, dim3(k), dim3(1024), 0, s, f, alpha, b, k, pl.wg_cols, pl.p_fixed, g.list, g.sbase, g.snum, g.hdr)
         const int nv = (b + 4095) / 4096;      // int4 loads per lane when 16 waves share the rows
         if (nv <= 1) PAMM_LAUNCH_GROUP(k_group_regs<1>);
         else if (nv <= 2) PAMM_LAUNCH_GROUP(k_group_regs<2>);
@@ -709,8 +753,8 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
         ScopedSpan span(kContract, s);
         const dim3 grid((unsigned)(pl.chunks * pl.wg_cols));
 #define PAMM_LAUNCH_CONTRACT(WV) \
-    hipLaunchKernelGGL((k_contract<TR, WV>), grid, dim3(256), 0, s, (const u32x4_t*)dY, g.list, b, pl.piece_rows, mch, m, \
-                       pl.wg_cols, g.partial)
+    hipLaunchKernelGGL((k_contract<TR, WV>), grid, dim3(256), 0, s, (const u32x4_t*)dY, g.list, g.hdr, mch, m, pl.wg_cols, \
+                       g.partial)
         if (pl.wave_groups == 1) PAMM_LAUNCH_CONTRACT(1);
         else if (pl.wave_groups == 2) PAMM_LAUNCH_CONTRACT(2);
         else PAMM_LAUNCH_CONTRACT(3);

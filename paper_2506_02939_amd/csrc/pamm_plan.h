@@ -86,8 +86,8 @@ inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt,
 // ---------------------------------------------------------------------------------------- grad
 
 struct GradPlan {
-    int piece_rows;       // P: the sorted row list is cut into chunks of P positions (a multiple of 16)
-    int64_t chunks;       // ceil(b / P)
+    int p_fixed;          // chunk size forced by PAMM_PIECE_ROWS (0: chosen on the device from the length of the list)
+    int64_t chunks;       // upper bound on the number of chunks the sorted list is cut into
     int64_t nslots;       // upper bound on piece numbers: chunks + k
     int col_groups;       // ceil(m / 512)
     int wave_groups;      // W: 512-column groups per wave (1..3); a workgroup of 4 waves covers 4*W groups of a row
@@ -95,7 +95,7 @@ struct GradPlan {
     int64_t kpad;         // k rounded up to a multiple of 16 (a whole number of MFMA steps for both element types)
     int slice_rows;       // rows per slice of the counting sort (1024 or 4096)
     int64_t nslices;      // ceil(b / slice_rows)
-    size_t off_list, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
+    size_t off_list, off_hdr, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
 };
 
 inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, GradPlan* p) {
@@ -113,15 +113,17 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     p->wg_cols = (p->col_groups + 4 * W - 1) / (4 * W);
     // One workgroup per (chunk, 4*W column groups).  All workgroups carry the same load, and measured on the
     // MI355X the contraction runs best as one even round: exactly one workgroup per CU (256 CUs), i.e. few, long
-    // chunks (4 waves per CU, each with >= 12 KiB of dY in flight).
-    int64_t P = (b * p->wg_cols + kNumCU - 1) / kNumCU;
-    P = (P + 15) / 16 * 16;
-    if (P < 16) P = 16;
-    if (P > 4096) P = 4096;
+    // chunks (4 waves per CU, each with >= 12 KiB of dY in flight).  The list only holds the rows with a non-zero
+    // weight, L <= b of them, so the chunk size P = clamp(roundup16(L * wg_cols / 256), 16, 4096) is set on the
+    // device; whatever L is, that gives at most max(ceil(256 / wg_cols), ceil(b / 4096)) + 1 chunks.
     const int p_env = env_int("PAMM_PIECE_ROWS");
-    if (p_env >= 16 && p_env <= 4096 && p_env % 16 == 0) P = p_env;
-    p->piece_rows = int(P);
-    p->chunks = (b + P - 1) / P;
+    p->p_fixed = (p_env >= 16 && p_env <= 4096 && p_env % 16 == 0) ? p_env : 0;
+    if (p->p_fixed) {
+        p->chunks = (b + p->p_fixed - 1) / p->p_fixed;
+    } else {
+        const int64_t even = (kNumCU + p->wg_cols - 1) / p->wg_cols, longest = (b + 4095) / 4096;
+        p->chunks = (even > longest ? even : longest) + 1;
+    }
     p->nslots = p->chunks + k;
     p->kpad = (k + 15) / 16 * 16;
     // Counting sort of the rows by generator: short slices spread the scattered list writes over many CUs, but every
@@ -130,6 +132,7 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     p->nslices = (b + p->slice_rows - 1) / p->slice_rows;
     size_t o = 0;
     p->off_list = o;    o = align_up(o + size_t(b + 16) * 16, 256);     // 16-byte entries, padded to a multiple of 16 entries
+    p->off_hdr = o;     o = align_up(o + 16, 256);                      // list length and chunk size, written by the grouping
     p->off_sbase = o;   o = align_up(o + size_t(k) * 4, 256);
     p->off_snum = o;    o = align_up(o + size_t(k) * 4, 256);
     p->off_table = o;   o = align_up(o + size_t(p->nslices) * size_t(k) * 4, 256);           // per-slice histograms

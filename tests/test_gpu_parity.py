@@ -251,6 +251,32 @@ def test_grad_clamps_out_of_range_assignments(pamm):
     assert torch.equal(a, c)
 
 
+@pytest.mark.parametrize("k", [6, 300, 2100], ids=["k6", "k300", "k2100"])
+def test_rows_with_zero_weight_are_left_out(pamm, oracle, k):
+    """Rows with alpha = 0 (dropped rows) are not in the sorted list at all: the result is that of the oracle, whatever
+    share of the batch they are, including all of it and none of it; their dY rows may even hold NaN."""
+    b, n, m = 5000, 64, 264
+    g = torch.Generator().manual_seed(17)
+    C = torch.randn(k, n, generator=g).to(torch.bfloat16)
+    dY = (0.1 * torch.randn(b, m, generator=g)).to(torch.bfloat16)
+    f = torch.randint(0, k, (b,), generator=g, dtype=torch.int32)
+    for share in (0.0, 0.7, 0.999, 1.0):
+        alpha = torch.rand(b, generator=g) + 0.5
+        dead = torch.rand(b, generator=g) < share
+        alpha[dead] = 0.0
+        dYp = dY.clone()
+        dYp[dead] = float("nan")                      # never read
+        _, O = oracle.grad(oracle.to_f64(C), f.numpy(), alpha.numpy().astype(np.float64), dY)
+        dW = pamm.grad(C.cuda(), f.cuda(), alpha.cuda(), dYp.cuda())
+        torch.cuda.synchronize()
+        got = dW.cpu().numpy()
+        assert np.isfinite(got).all()
+        if share == 1.0:
+            assert not got.any()
+        else:
+            assert rel_fro(got, O) <= TOL_DW["bf16"], (share, rel_fro(got, O))
+
+
 def test_step_can_be_captured_in_a_hip_graph(pamm):
     """pamm_compress_idx + pamm_grad allocate nothing, never synchronise and record no memset, so a caller can capture
     them.  Every replay (with eager work and synchronisations in between) must give the eager result bit for bit."""
