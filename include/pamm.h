@@ -131,7 +131,8 @@ pamm_status pamm_compress_idx_eps(const void *X, int64_t b, int64_t n, int64_t k
  *   dY     in   b x m, dtype dt
  *   dW     out  n x m fp32, overwritten
  * Rows are grouped by f with a stable counting sort and summed in fp32 in a fixed order, so
- * the result is bit-reproducible from call to call.  For PAMM_BF16 the contracted rows are
+ * the result is bit-reproducible from call to call.  Rows with alpha_i = 0 add nothing and are
+ * left out: their rows of dY are never read.  For PAMM_BF16 the contracted rows are
  * rounded to bf16 once before the C^T Btilde product (fp32 accumulation); for PAMM_F32 the
  * product is carried out in fp32 throughout.  Entries of f outside [0,k) are clamped into
  * range by the kernels rather than faulting.
