@@ -58,6 +58,9 @@ def main() -> int:
                          "256 MiB Infinity Cache from one step to the next (1 = every step re-reads the same buffers)")
     ap.add_argument("--eps", type=float, default=None,
                     help="time the path with the neighbourhood condition of Eq. 2 at this tolerance (default: none, eps = infinity)")
+    ap.add_argument("--dw", choices=["f32", "bf16"], default="f32",
+                    help="element type of the weight gradient (default fp32, the configuration the metric is quoted on)")
+    ap.add_argument("--dw-transposed", action="store_true", help="write the weight gradient as m x n instead of n x m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -85,13 +88,16 @@ def main() -> int:
 
     out = pamm.Compressed(torch.empty(k, n, dtype=X.dtype, device="cuda"), torch.empty(b, dtype=torch.int32, device="cuda"),
                           torch.empty(b, dtype=torch.float32, device="cuda"))
-    dW = torch.empty(n, m, dtype=torch.float32, device="cuda")
+    dw_kw = {}
+    if args.dw != "f32" or args.dw_transposed:
+        dw_kw = dict(out_dtype=torch.bfloat16 if args.dw == "bf16" else torch.float32, transposed=args.dw_transposed)
+    dW = torch.empty((m, n) if args.dw_transposed else (n, m), dtype=dw_kw.get("out_dtype", torch.float32), device="cuda")
     ws_c = torch.empty(pamm.compress_workspace(b, n, k, dt), dtype=torch.uint8, device="cuda")
     ws_g = torch.empty(pamm.grad_workspace(b, n, k, m, dt), dtype=torch.uint8, device="cuda")
 
     def step(i):
         pamm.compress(Xs[i % nsets], k, seed=i, eps=args.eps, out=out, ws=ws_c)      # fresh generators every step, as in training (App. F)
-        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g, **dw_kw)
 
     for i in range(args.warmup):
         step(i)
@@ -111,7 +117,7 @@ def main() -> int:
         ev[0].record()
         pamm.compress(Xs[i % nsets], k, seed=i, eps=args.eps, out=out, ws=ws_c)
         ev[1].record()
-        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g, **dw_kw)
         ev[2].record()
         torch.cuda.synchronize()
         tc += ev[0].elapsed_time(ev[1])
@@ -154,7 +160,8 @@ def main() -> int:
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "b": b, "n": n, "m": m, "k": k, "dtype": w.dtype,
                    "recipe": f"{w.centres} centres, sigma {w.sigma}, {w.structure}, pad {w.pad_frac}",
-                   "input_sets_rotated": nsets, "eps": args.eps},
+                   "input_sets_rotated": nsets, "eps": args.eps,
+                   "dW": args.dw + (" m x n" if args.dw_transposed else " n x m")},
         "ms_compress": round(tc, 4), "ms_grad": round(tg, 4),
         "roofline": roofline,
         "kernels": kernels,

@@ -55,6 +55,12 @@ typedef enum {
 
 typedef enum { PAMM_F32 = 0, PAMM_BF16 = 1 } pamm_dtype;   /* element type of X, C and dY */
 
+/* Orientation of the weight gradient written by pamm_grad_out. */
+typedef enum {
+    PAMM_DW_N_BY_M = 0,   /* n x m: O = A^T B as the paper writes it (Sec. 3.2); what pamm_grad writes */
+    PAMM_DW_M_BY_N = 1    /* m x n: its transpose, for a weight stored as outputs x inputs */
+} pamm_layout;
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *pamm_status_string(pamm_status s);
 
@@ -150,6 +156,22 @@ pamm_status pamm_grad(const void *C, const int32_t *f, const float *alpha, const
 pamm_status pamm_grad_eps(const void *C, const int32_t *f, const float *alpha, const int32_t *eta, const void *dY,
                           int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt,
                           float *dW, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * ApproxMM (Alg. 1) with a choice of element type and orientation for the weight gradient that the backward pass
+ * of the linear layer (Alg. 3) hands on, for callers that store the weight as outputs x inputs or keep its gradient
+ * in bf16.
+ *   eta     in   as pamm_grad_eps, or NULL for beta = 1 (then the call computes what pamm_grad computes)
+ *   out_dt       PAMM_F32, or PAMM_BF16: every element is the fp32 result rounded once, to nearest even
+ *   layout       PAMM_DW_N_BY_M (n x m) or PAMM_DW_M_BY_N (m x n); the values are the same, element for element
+ *   dW      out  n*m elements of out_dt in that orientation, overwritten
+ * PAMM_BF16 output needs an even row length of dW (PAMM_ERR_UNSUPPORTED otherwise; always true for PAMM_BF16
+ * inputs).  All other arguments, the workspace and the summation order as pamm_grad.
+ */
+pamm_status pamm_grad_out(const void *C, const int32_t *f, const float *alpha, const int32_t *eta, const void *dY,
+                          int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt,
+                          pamm_dtype out_dt, pamm_layout layout, void *dW,
+                          void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Test/benchmark hook: only the contraction stage of ApproxMM.

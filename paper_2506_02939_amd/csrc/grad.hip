@@ -607,9 +607,14 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
 // Tile order: workgroups are handed to the 8 XCDs round-robin, and every XCD has its own L2.  Workgroup number
 // bid therefore takes tile (bid % 8) * ceil(T/8) + bid / 8 of an order that walks the output in strips 8 tiles
 // wide, row by row: the 64 tiles an XCD works on at one time form an 8 x 8 block that shares 8 + 8 operand tiles.
-template <typename TR, int BK>
+//
+// The two operands enter alike, so the m x n orientation of the result (the layout of a weight stored as
+// outputs x inputs) is the same kernel with the operands exchanged.  OUT16 writes the result rounded to bf16
+// (round to nearest even): neighbouring lanes hold neighbouring columns, so each pair of lanes exchanges two of its
+// four rows and every lane stores two packed pairs instead of four single values.
+template <typename TR, int BK, bool OUT16>
 __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, const u32x4_t* __restrict__ Bt, int n, int m, int KC,
-                                             int tiles_n, int tiles_m, int per_xcd, float* __restrict__ dW) {
+                                             int tiles_n, int tiles_m, int per_xcd, void* __restrict__ dWv) {
     constexpr int RS = BK + 1, TILE = 128 * RS;
     constexpr int SUBS = 256 / BK;               // rows staged per pass of the workgroup
     constexpr int NI = 128 / SUBS;               // passes per operand tile
@@ -683,17 +688,45 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
     // library, and as ordinary stores its dirty lines are written back later, in the middle of the next kernels'
     // streams (measured: 25 % slower k_contract and k_score at the 7B-shaped layer).
     const int lw = l0 + wy * 64, cw = c0 + wx * 64;
+    if constexpr (!OUT16) {
+        float* __restrict__ dW = static_cast<float*>(dWv);
 #pragma unroll
-    for (int fa = 0; fa < 2; ++fa)
+        for (int fa = 0; fa < 2; ++fa)
 #pragma unroll
-        for (int fb = 0; fb < 2; ++fb) {
-            const int c = cw + 32 * fb + r;
+            for (int fb = 0; fb < 2; ++fb) {
+                const int c = cw + 32 * fb + r;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
-                if (l < n && c < m) __builtin_nontemporal_store(acc[fa][fb][i], &dW[size_t(l) * m + c]);
+                for (int i = 0; i < 16; ++i) {
+                    const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
+                    if (l < n && c < m) __builtin_nontemporal_store(acc[fa][fb][i], &dW[size_t(l) * m + c]);
+                }
             }
-        }
+    } else {
+        // even lane: keeps rows +0,+1 of each group of four and gets its neighbour's values of those rows (the column
+        // to its right); odd lane: keeps rows +2,+3 and gets the column to its left.  m is even, so a pair never
+        // straddles the edge.
+        uint32_t* __restrict__ dW = static_cast<uint32_t*>(dWv);
+        const bool odd = r & 1;
+#pragma unroll
+        for (int fa = 0; fa < 2; ++fa)
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb) {
+                const int c = cw + 32 * fb + (r & ~1);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float v0 = acc[fa][fb][4 * q], v1 = acc[fa][fb][4 * q + 1], v2 = acc[fa][fb][4 * q + 2],
+                                v3 = acc[fa][fb][4 * q + 3];
+                    const float got0 = __shfl_xor(odd ? v0 : v2, 1), got1 = __shfl_xor(odd ? v1 : v3, 1);
+                    const uint32_t p0 = odd ? pack_bf16(got0, v2) : pack_bf16(v0, got0);
+                    const uint32_t p1 = odd ? pack_bf16(got1, v3) : pack_bf16(v1, got1);
+                    const int l = lw + 32 * fa + 8 * q + 4 * g + (odd ? 2 : 0);
+                    if (c < m) {
+                        if (l < n) __builtin_nontemporal_store(p0, &dW[(size_t(l) * m + c) >> 1]);
+                        if (l + 1 < n) __builtin_nontemporal_store(p1, &dW[(size_t(l + 1) * m + c) >> 1]);
+                    }
+                }
+            }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------ host side
@@ -764,7 +797,7 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
 
 template <typename TR>
 static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void* C, int n, int m, int k, const int32_t* eta, int b,
-                            float* dW, hipStream_t s) {
+                            void* dW, bool out16, bool m_by_n, hipStream_t s) {
     const int KC = int(pl.kpad) / TR::kPerChunk;
     const int blocks_m = (m + 63) / 64, blocks_n = (n + 63) / 64;
     {
@@ -772,12 +805,19 @@ static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void
         hipLaunchKernelGGL((k_prep<TR>), dim3((unsigned)(blocks_m + blocks_n), (unsigned)(pl.kpad / 16)), dim3(256), 0, s, C,
                            g.partial, g.sbase, g.snum, n, m, k, KC, blocks_m, eta, b, g.ct, g.bt);
     }
-    const int tiles_n = (n + 127) / 128, tiles_m = (m + 127) / 128;
-    const int per_xcd = (tiles_n * tiles_m + 7) / 8;
+    // rows x cols of the result: n x m (O = A^T B), or m x n with the operands exchanged
+    const u32x4_t* rows_op = m_by_n ? g.bt : g.ct;
+    const u32x4_t* cols_op = m_by_n ? g.ct : g.bt;
+    const int nr = m_by_n ? m : n, nc = m_by_n ? n : m;
+    const int tiles_r = (nr + 127) / 128, tiles_c = (nc + 127) / 128;
+    const int per_xcd = (tiles_r * tiles_c + 7) / 8;
     {
         ScopedSpan span(kCtb, s);
-        hipLaunchKernelGGL((k_ctb<TR, 4>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, s, g.ct, g.bt, n, m, KC, tiles_n, tiles_m,
-                           per_xcd, dW);
+        const dim3 grid((unsigned)(per_xcd * 8));
+        if (out16)
+            hipLaunchKernelGGL((k_ctb<TR, 4, true>), grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, KC, tiles_r, tiles_c, per_xcd, dW);
+        else
+            hipLaunchKernelGGL((k_ctb<TR, 4, false>), grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, KC, tiles_r, tiles_c, per_xcd, dW);
     }
 }
 
@@ -808,10 +848,14 @@ extern "C" pamm_status pamm_contract(const int32_t* f, const float* alpha, const
 }
 
 static pamm_status grad_impl(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY, int64_t b,
-                             int64_t n, int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws, size_t ws_bytes, void* stream) {
+                             int64_t n, int64_t k, int64_t m, pamm_dtype dt, pamm_dtype out_dt, pamm_layout layout, void* dW,
+                             void* ws, size_t ws_bytes, void* stream) {
     GradPlan pl;
     pamm_status st = plan_grad(b, n, k, m, dt, &pl);
     if (st != PAMM_OK) return st;
+    if (!dtype_ok(out_dt) || (layout != PAMM_DW_N_BY_M && layout != PAMM_DW_M_BY_N)) return PAMM_ERR_UNSUPPORTED;
+    if (out_dt == PAMM_BF16 && (((layout == PAMM_DW_M_BY_N) ? n : m) & 1)) return PAMM_ERR_UNSUPPORTED;   // pairs of columns
+    const bool out16 = out_dt == PAMM_BF16, m_by_n = layout == PAMM_DW_M_BY_N;
     if (k > b) return PAMM_ERR_INVALID_ARG;
     if (!C || !f || !alpha || !dY || !dW) return PAMM_ERR_INVALID_ARG;
     if (!aligned16(C) || !aligned16(f) || !aligned16(alpha) || !aligned16(dY) || !aligned16(dW)) return PAMM_ERR_INVALID_ARG;
@@ -821,22 +865,29 @@ static pamm_status grad_impl(const void* C, const int32_t* f, const float* alpha
     GradBuffers g = carve(pl, (char*)ws);
     if (dt == PAMM_BF16) {
         launch_group_contract<Bf16>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-        launch_prep_ctb<Bf16>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, s);
+        launch_prep_ctb<Bf16>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, out16, m_by_n, s);
     } else {
         launch_group_contract<F32>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
-        launch_prep_ctb<F32>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, s);
+        launch_prep_ctb<F32>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, out16, m_by_n, s);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
 
 extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t n,
                                  int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws, size_t ws_bytes, void* stream) {
-    return grad_impl(C, f, alpha, nullptr, dY, b, n, k, m, dt, dW, ws, ws_bytes, stream);
+    return grad_impl(C, f, alpha, nullptr, dY, b, n, k, m, dt, PAMM_F32, PAMM_DW_N_BY_M, dW, ws, ws_bytes, stream);
 }
 
 extern "C" pamm_status pamm_grad_eps(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY,
                                      int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws,
                                      size_t ws_bytes, void* stream) {
     if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u)) return PAMM_ERR_INVALID_ARG;
-    return grad_impl(C, f, alpha, eta, dY, b, n, k, m, dt, dW, ws, ws_bytes, stream);
+    return grad_impl(C, f, alpha, eta, dY, b, n, k, m, dt, PAMM_F32, PAMM_DW_N_BY_M, dW, ws, ws_bytes, stream);
+}
+
+extern "C" pamm_status pamm_grad_out(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY,
+                                     int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, pamm_dtype out_dt,
+                                     pamm_layout layout, void* dW, void* ws, size_t ws_bytes, void* stream) {
+    if (eta && (reinterpret_cast<uintptr_t>(eta) & 3u)) return PAMM_ERR_INVALID_ARG;
+    return grad_impl(C, f, alpha, eta, dY, b, n, k, m, dt, out_dt, layout, dW, ws, ws_bytes, stream);
 }

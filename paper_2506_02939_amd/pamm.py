@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libpamm.so")
 PAMM_OK = 0
 PAMM_ERR_INVALID_ARG, PAMM_ERR_UNSUPPORTED, PAMM_ERR_WORKSPACE, PAMM_ERR_DEVICE = 1, 2, 3, 4
 PAMM_F32, PAMM_BF16 = 0, 1
+PAMM_DW_N_BY_M, PAMM_DW_M_BY_N = 0, 1
 
 EXPORTS = [
     "pamm_status_string", "pamm_compress_workspace", "pamm_grad_workspace", "pamm_sample_indices",
     "pamm_compress", "pamm_compress_idx", "pamm_compress_eps", "pamm_compress_idx_eps", "pamm_grad", "pamm_grad_eps",
-    "pamm_contract",
+    "pamm_grad_out", "pamm_contract",
     "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
 ]
 NUM_KERNELS = 8
@@ -61,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.pamm_grad.restype = ci
     lib.pamm_grad_eps.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_grad_eps.restype = ci
+    lib.pamm_grad_out.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, sz, vp]
+    lib.pamm_grad_out.restype = ci
     lib.pamm_contract.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_contract.restype = ci
     lib.pamm_profile_begin.argtypes = []
@@ -175,23 +178,35 @@ def compress(X: torch.Tensor, k: int, seed: int = 0, *, idx: torch.Tensor | None
 
 
 def grad(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, *, eta: torch.Tensor | None = None,
-         out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
-    """pamm_grad: dW (n x m, fp32) = C^T Btilde; with `eta` (device int32) pamm_grad_eps: beta C^T Btilde."""
+         out_dtype: torch.dtype | None = None, transposed: bool = False, out: torch.Tensor | None = None,
+         ws: torch.Tensor | None = None) -> torch.Tensor:
+    """pamm_grad: dW (n x m, fp32) = C^T Btilde; with `eta` (device int32) pamm_grad_eps: beta C^T Btilde.
+    With `out_dtype` (torch.float32 or torch.bfloat16) or `transposed` (dW as m x n) given: pamm_grad_out."""
     k, n = C.shape
     b, m = dY.shape
     dt = _dtype_code(dY)
     if C.dtype != dY.dtype:
         raise PammError(PAMM_ERR_UNSUPPORTED, "C and dY differ in element type")
+    plain = out_dtype is None and not transposed
+    odt = torch.float32 if out_dtype is None else out_dtype
+    shape = (m, n) if transposed else (n, m)
     if out is None:
-        out = torch.empty(n, m, dtype=torch.float32, device=dY.device)
+        out = torch.empty(*shape, dtype=odt, device=dY.device)
+    elif out.dtype != odt or tuple(out.shape) != shape:
+        raise ValueError(f"out must be {shape} of {odt}")
     ws = _workspace(grad_workspace(b, n, k, m, dt), dY.device, ws)
-    if eta is None:
-        st = lib.pamm_grad(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, dt, out.data_ptr(),
+    if not plain:
+        st = lib.pamm_grad_out(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), None if eta is None else _dev(eta, "eta"),
+                               _dev(dY, "dY"), b, n, k, m, dt, _dtype_code(out), PAMM_DW_M_BY_N if transposed else PAMM_DW_N_BY_M,
+                               _dev(out, "out"), ws.data_ptr(), ws.numel(), _stream())
+        _check(st, "pamm_grad_out")
+    elif eta is None:
+        st = lib.pamm_grad(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, dt, _dev(out, "out"),
                            ws.data_ptr(), ws.numel(), _stream())
         _check(st, "pamm_grad")
     else:
         st = lib.pamm_grad_eps(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(eta, "eta"), _dev(dY, "dY"), b, n, k, m, dt,
-                               out.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+                               _dev(out, "out"), ws.data_ptr(), ws.numel(), _stream())
         _check(st, "pamm_grad_eps")
     return out
 

@@ -158,6 +158,27 @@ def test_tolerance_argument_checks(pamm):
     assert _grad_eps(P, ws_bytes=1024) == P.PAMM_ERR_WORKSPACE
 
 
+def _grad_out(pamm, C=A, f=A, alpha=A, eta=None, dY=A, b=64, n=64, k=4, m=64, dt=1, out_dt=1, layout=1, dW=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_grad_out(C, f, alpha, eta, dY, b, n, k, m, dt, out_dt, layout, dW, ws, ws_bytes, None)
+
+
+def test_grad_out_argument_checks(pamm):
+    """Element type and orientation of dW are checked on the host like everything else; eta may be absent."""
+    P = pamm
+    assert _grad_out(P, out_dt=2) == P.PAMM_ERR_UNSUPPORTED
+    assert _grad_out(P, layout=2) == P.PAMM_ERR_UNSUPPORTED
+    assert _grad_out(P, layout=-1) == P.PAMM_ERR_UNSUPPORTED
+    assert _grad_out(P, eta=A + 2) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_out(P, dW=None) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_out(P, dW=A + 4) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_out(P, m=12) == P.PAMM_ERR_UNSUPPORTED
+    assert _grad_out(P, k=65) == P.PAMM_ERR_INVALID_ARG
+    assert _grad_out(P, ws=None) == P.PAMM_ERR_WORKSPACE
+    assert _grad_out(P, eta=A, ws_bytes=1024) == P.PAMM_ERR_WORKSPACE
+    # fp32 inputs with rows of 4k+... elements: a bf16 result needs an even row length, which multiples of 4 always are
+    assert _grad_out(P, dt=0, n=4, m=4, out_dt=1, layout=0, ws=None) == P.PAMM_ERR_WORKSPACE
+
+
 def test_binding_refuses_cpu_tensors(pamm):
     import torch
 
