@@ -28,8 +28,9 @@
  *     stream).  The calls do not synchronise the stream: outputs are valid once the
  *     stream has reached the end of the enqueued work.  Scratch memory comes from the
  *     caller through (ws, ws_bytes), sized by the *_workspace queries; the compute
- *     calls allocate no device memory.  (pamm_compress keeps a small pinned host ring
- *     for the sampled indices, created on first use per device.)
+ *     calls allocate no device memory.  (Up to 512 sampled indices travel in a kernel's
+ *     argument block; for larger k pamm_compress keeps a small pinned host ring for them,
+ *     created on first use per device.)
  *   - Errors are return codes.  All argument checks happen on the host before
  *     anything is enqueued; on a non-OK return nothing was enqueued and no output
  *     was touched, except PAMM_ERR_DEVICE (a HIP call failed part-way).

@@ -81,15 +81,18 @@ struct Best {
 };
 
 // ------------------------------------------------------------------------------------------------
-// k_gather: one workgroup per generator.
+// k_gather: one workgroup per generator.  The row numbers come from memory (caller-chosen generators, or more than
+// kArgGenerators sampled ones) or ride in the kernel's own argument block (k_gather_arg): the sampled indices then
+// need no buffer that outlives the call, and a captured launch replays with the indices it was captured with.
+constexpr int kArgGenerators = 512;
+struct IdxByValue { int32_t v[kArgGenerators]; };
+
 template <typename TR>
-__global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, const int32_t* __restrict__ idx_in, int b, int nch,
-                                                u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
-                                                double* __restrict__ cn2, unsigned long long* __restrict__ hash,
-                                                int32_t* __restrict__ eta) {
+__device__ __forceinline__ void gather_row(const u32x4_t* __restrict__ X, int src, int b, int nch, u32x4_t* __restrict__ C,
+                                           int32_t* __restrict__ idx_out, float* __restrict__ inv, double* __restrict__ cn2,
+                                           unsigned long long* __restrict__ hash, int32_t* __restrict__ eta) {
     const int j = blockIdx.x;
     if (eta && j == 0 && threadIdx.x == 0) *eta = 0;          // rows dropped by the neighbourhood condition: counted later
-    int src = idx_in[j];
     src = src < 0 ? 0 : (src >= b ? b - 1 : src);
     const u32x4_t* xr = X + size_t(src) * nch;
     u32x4_t* cr = C + size_t(j) * nch;
@@ -123,6 +126,22 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
         hash[j] = sh[0] + sh[1] + sh[2] + sh[3];
         idx_out[j] = src;
     }
+}
+
+template <typename TR>
+__global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, const int32_t* __restrict__ idx_in, int b, int nch,
+                                                u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
+                                                double* __restrict__ cn2, unsigned long long* __restrict__ hash,
+                                                int32_t* __restrict__ eta) {
+    gather_row<TR>(X, idx_in[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
+}
+
+template <typename TR>
+__global__ __launch_bounds__(256) void k_gather_arg(const u32x4_t* __restrict__ X, const IdxByValue idx_in, int b, int nch,
+                                                    u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
+                                                    double* __restrict__ cn2, unsigned long long* __restrict__ hash,
+                                                    int32_t* __restrict__ eta) {
+    gather_row<TR>(X, idx_in.v[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -677,8 +696,9 @@ static void launch_score(const CompressPlan& pl, const ScoreArgs& a, hipStream_t
 }
 
 template <typename TR>
-static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, int n, int k, const int32_t* idx_src, double keep,
-                                void* C, int32_t* f, float* alpha, int32_t* eta, char* ws, hipStream_t s) {
+static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, int n, int k, const int32_t* idx_src,
+                                const IdxByValue* idx_arg, double keep, void* C, int32_t* f, float* alpha, int32_t* eta, char* ws,
+                                hipStream_t s) {
     const int nch = n / TR::kPerChunk;
     int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
     float* inv = reinterpret_cast<float*>(ws + pl.off_inv);
@@ -688,7 +708,12 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
 
     {
         ScopedSpan span(kGather, s);
-        hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_src, b, nch, (u32x4_t*)C, idx, inv, cn2, hash, eta);
+        if (idx_arg)
+            hipLaunchKernelGGL((k_gather_arg<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, *idx_arg, b, nch, (u32x4_t*)C, idx, inv,
+                               cn2, hash, eta);
+        else
+            hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_src, b, nch, (u32x4_t*)C, idx, inv, cn2,
+                               hash, eta);
     }
     {
         ScopedSpan span(kScore, s);
@@ -713,7 +738,7 @@ static pamm_status check_compress_args(const void* X, int64_t b, int64_t n, int6
     return PAMM_OK;
 }
 
-// ---- pinned ring that carries sampled indices to the gather kernel without a copy or a sync ----
+// ---- pinned ring that carries more than kArgGenerators sampled indices to the gather kernel without a copy or a sync ----
 constexpr int kRingSlots = 32;
 constexpr int kMaxDevices = 16;
 struct IdxRing {
@@ -746,8 +771,9 @@ static pamm_status compress_idx_impl(const void* X, int64_t b, int64_t n, int64_
     if (st != PAMM_OK) return st;
     if (!idx_dev) return PAMM_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (dt == PAMM_BF16) return run_compress<Bf16>(pl, X, int(b), int(n), int(k), idx_dev, keep, C, f, alpha, eta, (char*)ws, s);
-    return run_compress<F32>(pl, X, int(b), int(n), int(k), idx_dev, keep, C, f, alpha, eta, (char*)ws, s);
+    if (dt == PAMM_BF16)
+        return run_compress<Bf16>(pl, X, int(b), int(n), int(k), idx_dev, nullptr, keep, C, f, alpha, eta, (char*)ws, s);
+    return run_compress<F32>(pl, X, int(b), int(n), int(k), idx_dev, nullptr, keep, C, f, alpha, eta, (char*)ws, s);
 }
 
 static pamm_status compress_seed_impl(const void* X, int64_t b, int64_t n, int64_t k, uint64_t seed, double keep, pamm_dtype dt,
@@ -756,6 +782,16 @@ static pamm_status compress_seed_impl(const void* X, int64_t b, int64_t n, int64
     pamm_status st = check_compress_args(X, b, n, k, dt, C, f, alpha, ws, ws_bytes, &pl);
     if (st != PAMM_OK) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    if (k <= kArgGenerators) {          // the sampled row numbers travel in the gather kernel's argument block
+        IdxByValue ia;
+        st = pamm_sample_indices(b, k, seed, ia.v);
+        if (st != PAMM_OK) return st;
+        for (int64_t j = k; j < kArgGenerators; ++j) ia.v[j] = 0;
+        if (dt == PAMM_BF16)
+            return run_compress<Bf16>(pl, X, int(b), int(n), int(k), nullptr, &ia, keep, C, f, alpha, eta, (char*)ws, s);
+        return run_compress<F32>(pl, X, int(b), int(n), int(k), nullptr, &ia, keep, C, f, alpha, eta, (char*)ws, s);
+    }
 
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return PAMM_ERR_DEVICE;
@@ -783,8 +819,8 @@ static pamm_status compress_seed_impl(const void* X, int64_t b, int64_t n, int64
     if (st != PAMM_OK) return st;
     const int32_t* didx = ring.dev + size_t(slot) * kMaxGenerators;
 
-    if (dt == PAMM_BF16) st = run_compress<Bf16>(pl, X, int(b), int(n), int(k), didx, keep, C, f, alpha, eta, (char*)ws, s);
-    else st = run_compress<F32>(pl, X, int(b), int(n), int(k), didx, keep, C, f, alpha, eta, (char*)ws, s);
+    if (dt == PAMM_BF16) st = run_compress<Bf16>(pl, X, int(b), int(n), int(k), didx, nullptr, keep, C, f, alpha, eta, (char*)ws, s);
+    else st = run_compress<F32>(pl, X, int(b), int(n), int(k), didx, nullptr, keep, C, f, alpha, eta, (char*)ws, s);
     if (hipEventRecord(ring.ev[slot], s) != hipSuccess) return PAMM_ERR_DEVICE;
     ring.used[slot] = true;
     return st;

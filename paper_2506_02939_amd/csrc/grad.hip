@@ -1,12 +1,14 @@
-// pamm_grad / pamm_contract: Alg. 1, procedure ApproxMM.
+// pamm_grad / pamm_grad_eps / pamm_grad_out / pamm_contract: Alg. 1, procedure ApproxMM.
 //
-// Three launches on the caller's stream:
-//   k_group     stable grouping of the rows by f(i): workgroup j lists the rows of generator j in increasing i
-//               and cuts the list into pieces of at most P rows
-//   k_contract  streams dY once: one wave per (piece, 512 columns) sums alpha_i * dY_i in registers, in list
-//               order, and writes one fp32 partial row.  No atomics, no LDS; bit-reproducible.
-//   k_ctb       dW = C^T Btilde on the matrix cores; Btilde_j is formed on the fly as the sum of generator j's
-//               partial rows
+// Launches on the caller's stream:
+//   grouping    stable grouping of the rows by f(i) into one sorted list of 16-byte entries, cut into chunks of P
+//               positions: a counting sort (k_sort_one for b <= 16384, k_hist + k_scatter above that) for
+//               k <= 2048, one workgroup per generator (k_group_regs / k_group_stream) for larger k
+//   k_contract  streams dY once: one wave per (chunk, 512 columns) sums alpha_i * dY_i in registers, in list
+//               order, and writes one fp32 partial row per piece.  No atomics, no LDS; bit-reproducible.
+//   k_prep      Btilde_j = sum of generator j's partial rows (times beta); both operands of the product laid out
+//               with the generator index contiguous
+//   k_ctb       dW = C^T Btilde on the matrix cores
 #include <hip/hip_runtime.h>
 
 #include "pamm_device.h"
@@ -353,6 +355,104 @@ __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, c
             const int pos = tot[key[c]] + atomicAdd(&wh[wave * k + key[c]], 1);
             list[pos] = list_entry(i0 + c, al[c], key[c]);
             if (pos == L - 1) pad_list(list, L, i0 + c, key[c]);
+        }
+    }
+}
+
+// The same counting sort for batches of at most 4096 Q rows (Q = 1, 2, 4: b <= 16384) in ONE workgroup of 16 waves
+// and one kernel: the whole histogram is the workgroup's own, so nothing passes through memory between the two
+// phases and one dispatch latency is saved (the small shapes are bound by those).  Wave w owns the rows
+// [256 Q w, 256 Q (w + 1)).
+template <int Q>
+__global__ __launch_bounds__(1024) void k_sort_one(const int32_t* __restrict__ f, const float* __restrict__ alpha, int b, int k,
+                                                   int wg_cols, int p_fixed, u32x4_t* __restrict__ list,
+                                                   int32_t* __restrict__ sbase, int32_t* __restrict__ snum,
+                                                   int32_t* __restrict__ hdr) {
+    constexpr int NT = 1024, NWV = 16;
+    extern __shared__ int lds[];
+    int* wh = lds;                 // [NWV][k] per-wave counts, later per-wave next free position inside the generator's list
+    int* tot = lds + NWV * k;      // [k]      rows per generator, later start of the generator's list
+    int* cnt = tot + k;            // [k]      rows per generator
+    __shared__ int wsum[NWV];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r0 = wave * (256 * Q);
+
+    int key[Q][4];
+    float al[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int i0 = r0 + q * 256 + 4 * lane;
+        load_keys(f, alpha, i0, b, k, key[q]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) al[q][c] = alpha[max(0, min(i0 + c, b - 1))];
+    }
+    for (int q = tid; q < (NWV + 2) * k; q += NT) wh[q] = 0;      // wh, tot and cnt are contiguous
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (key[q][c] < k) atomicAdd(&wh[wave * k + key[q][c]], 1);
+    __syncthreads();
+    for (int j = tid; j < k; j += NT) {
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) {
+            const int c = wh[w * k + j];
+            wh[w * k + j] = run;
+            run += c;
+        }
+        tot[j] = run;
+    }
+    __syncthreads();
+
+    // exclusive scan of tot[] over the generators, NT at a time
+    int carry = 0;
+    for (int base = 0; base < k; base += NT) {
+        const int j = base + tid;
+        const int x = j < k ? tot[j] : 0;
+        int incl = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o);
+            if (lane >= o) incl += y;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        int wpre = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) {
+            const int v = wsum[w];
+            wpre += w < wave ? v : 0;
+            all += v;
+        }
+        const int start = carry + wpre + incl - x;
+        if (j < k) {
+            tot[j] = start;
+            cnt[j] = x;
+        }
+        carry += all;
+        __syncthreads();
+    }
+    const int L = carry;
+    const int P = piece_rows_for(L, wg_cols, p_fixed);
+    for (int j = tid; j < k; j += NT) {
+        const int start = tot[j], x = cnt[j];
+        sbase[j] = start / P + j;
+        snum[j] = x > 0 ? (start + x - 1) / P - start / P + 1 : 0;
+    }
+    if (tid == 0) { hdr[0] = L; hdr[1] = P; }
+
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int i0 = r0 + q * 256 + 4 * lane;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (key[q][c] < k) {
+                const int pos = tot[key[q][c]] + atomicAdd(&wh[wave * k + key[q][c]], 1);
+                list[pos] = list_entry(i0 + c, al[q][c], key[q][c]);
+                if (pos == L - 1) pad_list(list, L, i0 + c, key[q][c]);
+            }
         }
     }
 }
@@ -757,7 +857,16 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
                                   int b, int k, int m, hipStream_t s) {
     {
         ScopedSpan span(kGroup, s);
-        if (k <= kScatterMaxK) {
+        if (k <= kScatterMaxK && b <= pl.sort_one_rows) {
+            const size_t lds = size_t(16 + 2) * k * 4;
+#define PAMM_LAUNCH_SORT_ONE(QV) \
+    hipLaunchKernelGGL(k_sort_one<QV>, dim3(1), dim3(1024), lds, s, f, alpha, b, k, pl.wg_cols, pl.p_fixed, g.list, g.sbase, g.snum, \
+                       g.hdr)
+            if (b <= 4096) PAMM_LAUNCH_SORT_ONE(1);
+            else if (b <= 8192) PAMM_LAUNCH_SORT_ONE(2);
+            else PAMM_LAUNCH_SORT_ONE(4);
+#undef PAMM_LAUNCH_SORT_ONE
+        } else if (k <= kScatterMaxK) {
             const int nslices = int(pl.nslices);
             if (pl.slice_rows == 1024) {
                 hipLaunchKernelGGL(k_hist<256>, dim3(nslices), dim3(256), size_t(k) * 4, s, f, alpha, b, k, g.table);

@@ -24,6 +24,7 @@ inline bool dtype_ok(pamm_dtype dt) { return dt == PAMM_F32 || dt == PAMM_BF16; 
 //   PAMM_SCORE_NW    waves per workgroup in k_score (2, 4 or 8)
 //   PAMM_PIECE_ROWS  list positions per chunk in k_contract (a multiple of 16, 16..4096)
 //   PAMM_CONTRACT_W  512-column groups per wave in k_contract (1..3)
+//   PAMM_SORT_ONE    largest b sorted by the single-workgroup kernel (1..16384)
 inline int env_int(const char* name) {
     const char* v = getenv(name);
     return v ? atoi(v) : 0;
@@ -90,6 +91,7 @@ struct GradPlan {
     int64_t chunks;       // upper bound on the number of chunks the sorted list is cut into
     int64_t nslots;       // upper bound on piece numbers: chunks + k
     int col_groups;       // ceil(m / 512)
+    int sort_one_rows;    // batches up to this many rows are sorted by one workgroup in one kernel
     int wave_groups;      // W: 512-column groups per wave (1..3); a workgroup of 4 waves covers 4*W groups of a row
     int wg_cols;          // workgroups side by side along a row: ceil(col_groups / (4*W))
     int64_t kpad;         // k rounded up to a multiple of 16 (a whole number of MFMA steps for both element types)
@@ -110,6 +112,8 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     const int w_env = env_int("PAMM_CONTRACT_W");
     if (w_env >= 1 && w_env <= 3) W = w_env;
     p->wave_groups = W;
+    const int so_env = env_int("PAMM_SORT_ONE");
+    p->sort_one_rows = (so_env >= 1 && so_env <= 16384) ? so_env : 8192;
     p->wg_cols = (p->col_groups + 4 * W - 1) / (4 * W);
     // One workgroup per (chunk, 4*W column groups).  All workgroups carry the same load, and measured on the
     // MI355X the contraction runs best as one even round: exactly one workgroup per CU (256 CUs), i.e. few, long
