@@ -11,6 +11,8 @@
 //   k_ctb       dW = C^T Btilde on the matrix cores
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "pamm_device.h"
 #include "pamm_plan.h"
 #include "pamm_profile.h"
@@ -659,28 +661,49 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
     const bool is_b = int(blockIdx.x) < blocks_m;
     const int x0 = (is_b ? blockIdx.x : blockIdx.x - blocks_m) * 64;      // first column (of dY) or hidden index
     const int extent = is_b ? m : n;
+    // thread t fills (column t % 64, generator t / 64 + 4 i), i = 0..3: the generator is the same for a whole wave
+    const int xx = tid & 63, x = x0 + xx;
+    if (is_b) {
+        // The four sums of a thread advance together, four or eight pieces each per round, so that a round costs one
+        // memory latency for 16 or 32 loads (the number of pieces per generator varies; the loop runs to the longest of the four).
+        // Slots past a generator's last piece re-read a valid address and count as 0.
+        const int xs = min(x, m - 1);
+        int base[4], np[4], npmax = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int pair = tid + 256 * i;
-        const int xx = pair & 63, jj = pair >> 6;                        // jj is the same for a whole wave
-        const int x = x0 + xx, j = j0 + jj;
-        float v = 0.f;
-        if (j < k && x < extent) {
-            if (is_b) {
-                const int base = sbase[j], np = snum[j];
-                for (int t = 0; t < np; t += 4) {          // four pieces in flight; slots past the last one re-read it with weight 0
-                    float p4[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) p4[q] = partial[size_t(base + min(t + q, np - 1)) * m + x];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) v += (t + q < np) ? p4[q] : 0.f;
-                }
-                v *= beta;
-            } else {
-                v = PrepIo<TR>::load_c(C, size_t(j) * n + x);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int j = j0 + (tid >> 6) + 4 * i;
+            const bool ok = j < k && x < m;
+            base[i] = ok ? sbase[j] : 0;
+            np[i] = ok ? snum[j] : 0;
+            npmax = max(npmax, np[i]);
         }
-        tile[xx][jj] = v;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        auto rounds = [&](auto pieces_per_round) {
+            constexpr int R = decltype(pieces_per_round)::value;
+            for (int t = 0; t < npmax; t += R) {
+                float p[4][R];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int q = 0; q < R; ++q) p[i][q] = partial[size_t(base[i] + max(0, min(t + q, np[i] - 1))) * m + xs];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int q = 0; q < R; ++q) v[i] += (t + q < np[i]) ? p[i][q] : 0.f;
+            }
+        };
+        // long lists of pieces (few generators, small batches) are bound by the number of rounds; short ones by the
+        // loads themselves, of which the wider round issues more than needed
+        if (npmax > 4) rounds(std::integral_constant<int, 8>{});
+        else rounds(std::integral_constant<int, 4>{});
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[xx][(tid >> 6) + 4 * i] = v[i] * beta;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int jj = (tid >> 6) + 4 * i, j = j0 + jj;
+            tile[xx][jj] = (j < k && x < n) ? PrepIo<TR>::load_c(C, size_t(j) * n + x) : 0.f;
+        }
     }
     __syncthreads();
     constexpr int CP = PrepIo<TR>::kChunksPer16;
