@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--dw", choices=["f32", "bf16"], default="f32",
                     help="element type of the weight gradient (default fp32, the configuration the metric is quoted on)")
     ap.add_argument("--dw-transposed", action="store_true", help="write the weight gradient as m x n instead of n x m")
+    ap.add_argument("--layer", action="store_true",
+                    help="also time the forward + backward pass of the linear layer of Alg. 2-3 (exact products through the "
+                         "vendor BLAS) against the same layer with the exact weight gradient; adds a \"layer\" object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -189,6 +192,33 @@ def main() -> int:
         gms = (time.perf_counter() - g0) * 1e3 / reps_g
         result["exact_gemm"] = {"ms": round(gms, 4), "tokens_per_s": round(b / (gms * 1e-3), 1),
                                 "TFLOPs": round(2.0 * b * n * m / (gms * 1e-3) / 1e12, 1), "kind": "torch.matmul(X^T, dY), same GPU"}
+
+    if args.layer:
+        from paper_2506_02939_amd import linear
+
+        Xl = X.detach().clone().requires_grad_(True)
+        Wl = (torch.randn(n, m, device="cuda") / n ** 0.5).to(X.dtype).requires_grad_(True)
+
+        def layer_step(i, approx):
+            Xl.grad = None
+            Wl.grad = None
+            Z = linear.pamm_linear(Xl, Wl, k=k, seed=i, eps=args.eps) if approx else torch.matmul(Xl, Wl)
+            Z.backward(dY)
+
+        layer = {}
+        for approx in (True, False):
+            for i in range(3):
+                layer_step(i, approx)
+            torch.cuda.synchronize()
+            l0 = time.perf_counter()
+            reps_l = 10
+            for i in range(reps_l):
+                layer_step(i, approx)
+            torch.cuda.synchronize()
+            layer["ms_pamm" if approx else "ms_exact"] = round((time.perf_counter() - l0) * 1e3 / reps_l, 4)
+        layer["what"] = "Z = X W, backward with dZ = dY: dX exact, dW by PAMM (ms_pamm) or exact (ms_exact); GEMMs by torch.matmul"
+        result["layer"] = layer
+        del Xl, Wl
 
     if not args.no_cpu_baseline:
         from oracle import pamm_oracle

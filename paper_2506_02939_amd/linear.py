@@ -1,0 +1,66 @@
+"""A linear layer that keeps its input in PAMM's compressed form (Alg. 2: forward pass, Alg. 3: backward pass).
+
+Forward:  Z = X W, then (C, f, alpha) = Compress(flatten(X)); only C, f, alpha (and W) are kept for the backward pass,
+          k n + 2 b numbers instead of the b n of X (App. J).
+Backward: dW~ = ApproxMM(C, f, alpha, flatten(dZ)),  dX = dZ W^T (exact).
+
+Compress and ApproxMM are the library's calls (pamm.compress / pamm.grad, every step in its HIP kernels).  The two
+exact products are ordinary dense GEMMs and go through torch.matmul, i.e. the vendor BLAS; they are not part of the
+method.  Nothing here has a CPU path: tensors must live on the GPU.
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+from . import pamm
+
+
+def generators_for(b: int, r: float) -> int:
+    """k = ceil(r b), at least 1 and at most b (Sec. 4.1)."""
+    return max(1, min(b, math.ceil(r * b)))
+
+
+class _PammLinear(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, X, W, k, seed, eps, out_by_in):
+        n = X.shape[-1]
+        x2 = X.reshape(-1, n)
+        if not x2.is_contiguous():
+            x2 = x2.contiguous()
+        Z = torch.matmul(X, W.t() if out_by_in else W)
+        comp = pamm.compress(x2.detach(), k, seed=seed, eps=eps)
+        saved = [comp.C, comp.f, comp.alpha, W] + ([comp.eta] if comp.eta is not None else [])
+        ctx.save_for_backward(*saved)
+        ctx.out_by_in = out_by_in
+        ctx.x_shape = X.shape
+        return Z
+
+    @staticmethod
+    def backward(ctx, dZ):
+        C, f, alpha, W = ctx.saved_tensors[:4]
+        eta = ctx.saved_tensors[4] if len(ctx.saved_tensors) > 4 else None
+        dX = dW = None
+        if ctx.needs_input_grad[1]:
+            dz2 = dZ.reshape(-1, dZ.shape[-1])
+            if not dz2.is_contiguous():
+                dz2 = dz2.contiguous()
+            if dz2.dtype != C.dtype:
+                dz2 = dz2.to(C.dtype)
+            dW = pamm.grad(C, f, alpha, dz2, eta=eta, out_dtype=W.dtype, transposed=ctx.out_by_in)
+        if ctx.needs_input_grad[0]:
+            dX = torch.matmul(dZ, W if ctx.out_by_in else W.t()).reshape(ctx.x_shape)
+        return dX, dW, None, None, None, None
+
+
+def pamm_linear(X: torch.Tensor, W: torch.Tensor, *, r: float | None = 1.0 / 512, k: int | None = None, seed: int = 0,
+                eps: float | None = None, out_by_in: bool = False) -> torch.Tensor:
+    """Z = X W for X of shape (..., n) and W of shape n x m (the paper's orientation), or, with `out_by_in`, W of
+    shape m x n and Z = X W^T (the orientation of torch.nn.Linear.weight).  In the backward pass the gradient of W is
+    PAMM's estimate from k = ceil(r b) generators (or `k` as given) sampled with `seed`; `eps` switches the
+    neighbourhood condition of Eq. 2 and the factor beta on.  The gradient of X is exact.  A training loop passes a
+    fresh seed every step (Alg. 1 samples anew on every call)."""
+    b = X.numel() // X.shape[-1]
+    kk = generators_for(b, r) if k is None else k
+    return _PammLinear.apply(X, W, kk, seed, eps, out_by_in)
