@@ -323,6 +323,10 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     constexpr int XSLOT = TT * 256;      // chunks per X slot (TT fragments of 32 rows x 8 chunks)
     constexpr int D = 4;                 // X ring depth in registers (super-steps)
     constexpr int UN = SS > D ? SS : D;  // super-steps per unrolled body: a multiple of SS and of D
+    // Stages of C in flight in registers.  Short stages (TG >= 4: one or two super-steps) are over before a load from
+    // L2 has come back, so their loads are issued two stages ahead; the register slot of a stage is its parity,
+    // which is static when the unrolled body holds an even number of stages.
+    constexpr int PD = (UN / SS) % 2 == 0 ? 2 : 1;
     static_assert(GB * CPS % NT == 0, "stage does not divide over the threads");
 
     __shared__ u32x4_t lds_raw[2 * CBUF + NW * 2 * XSLOT];
@@ -333,8 +337,16 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     u32x4_t* const lds_x = lds_raw + 2 * CBUF + wave * (2 * XSLOT);         // [2][XSLOT], private to this wave
-    const int cb = blockIdx.x % ncb;
-    const int rt = blockIdx.x / ncb;
+    // Workgroups are handed to the 8 XCDs round-robin and every XCD has its own L2.  With several column blocks the
+    // workgroups of one row tile (which stream the same rows of X) take consecutive places in the sequence of ONE XCD,
+    // so that X comes from HBM once and from that L2 for the other column blocks.
+    int cb = 0, rt = blockIdx.x;
+    if (ncb > 1) {
+        const int xcd = blockIdx.x % 8, q = blockIdx.x / 8;
+        cb = q % ncb;
+        rt = (q / ncb) * 8 + xcd;
+        if (rt * (32 * TT * NW) >= b) return;          // the grid is rounded up to whole groups of 8 row tiles
+    }
     const int gen0 = cb * GB;
 
     if (tid == 0) { redo_count = 0; drop_count = 0; }          // published by the barriers of the main loop
@@ -374,14 +386,17 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     // Every workgroup walks the hidden dimension from a different starting window and wraps around (a dot product
     // does not care where it starts).  Without this all workgroups sit at the same column of their rows at the same
     // time, and since rows are a power of two apart the whole chip then leans on a few memory channels.
-    const int rot = (rt * 5) % nss;
+    // With several column blocks the workgroups of one XCD walk in step instead (one starting window per XCD): between
+    // them they then hold one window of all of C and of their rows of X in that XCD's L2 at a time, each line fetched
+    // once and hit by the others; walking apart, every workgroup's pass over its block of C missed the L2.
+    const int rot = ncb > 1 ? int(blockIdx.x % 8) * (nss / 8) % nss : (rt * 5) % nss;
     auto turned = [&](int v) {                   // walk position -> window of the row; positions past the end repeat the last
         const int a = min(v, nss - 1) + rot;
         return a >= nss ? a - nss : a;
     };
 
-    u32x4_t creg[CLOADS];
-    auto load_c = [&](int stage) {
+    u32x4_t creg[PD][CLOADS];
+    auto load_c = [&](int stage, int slot) {      // stages past the last one re-read the last window (never stored)
 #pragma unroll
         for (int i = 0; i < CLOADS; ++i) {
             const int q = tid + NT * i;
@@ -390,14 +405,14 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
             // Clamped addresses, no guard and no mask: a guarded load costs a branch per chunk, and a mask makes
             // the compiler wait for the load where it is issued.  Rows past the last generator are ignored by
             // the epilogue; chunks past the end of a row meet zero chunks of X.
-            creg[i] = C[size_t(min(j, k - 1)) * nch + min(c, nch - 1)];
+            creg[slot][i] = C[size_t(min(j, k - 1)) * nch + min(c, nch - 1)];
         }
     };
-    auto store_c = [&](int buf) {
+    auto store_c = [&](int buf, int slot) {
 #pragma unroll
         for (int i = 0; i < CLOADS; ++i) {
             const int q = tid + NT * i;
-            lds_c[buf * CBUF + (q / CPS) * RS + (q % CPS)] = creg[i];
+            lds_c[buf * CBUF + (q / CPS) * RS + (q % CPS)] = creg[slot][i];
         }
     };
     u32x4_t xr[D][TT][4];
@@ -435,10 +450,11 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         }
     };
 
-    load_c(0);
+    load_c(0, 0);
+    if (PD == 2) load_c(1, 1);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
-    store_c(0);
+    store_c(0, 0);
     stash_x(xr[0], 0, true);
     __syncthreads();
 
@@ -448,9 +464,9 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 #pragma unroll
         for (int p = 0; p < UN; ++p) {
             const int gs = bi * UN + p;                      // super-step
-            if (p % SS == 0) {                               // a stage of C begins
+            if (p % SS == 0) {                               // a stage of C begins: its register slot is free again
                 stage = gs / SS;
-                if (stage + 1 < nstages) load_c(stage + 1);
+                load_c(stage + PD, (p / SS) % PD);           // issued on every path, so that waits stay counted, not full
             }
             load_x(xr[(p + D - 1) % D], gs + D - 1);
             stash_x(xr[(p + 1) % D], (gs + 1) & 1, gs + 1 < nss);      // next super-step's tokens into the other slot
@@ -475,7 +491,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 }
             }
             if (p % SS == SS - 1) {                          // the stage ends: publish the next one
-                if (stage + 1 < nstages) store_c(buf ^ 1);
+                if (stage + 1 < nstages) store_c(buf ^ 1, (p / SS + 1) % PD);
                 __syncthreads();
                 buf ^= 1;
             } else {
@@ -662,7 +678,7 @@ struct ScoreArgs {
 
 template <typename TR, int TG, int TT, int NW, bool FUSED>
 static void launch_score_cfg(const CompressPlan& pl, const ScoreArgs& a, hipStream_t s) {
-    dim3 grid((unsigned)(pl.row_tiles * pl.ncb));
+    dim3 grid((unsigned)(pl.ncb > 1 ? (pl.row_tiles + 7) / 8 * 8 * pl.ncb : pl.row_tiles));
     if (a.nch % 8 == 0)      // every row is a whole number of 128-byte super-steps
         hipLaunchKernelGGL((k_score<TR, TG, TT, NW, true, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
                            (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
