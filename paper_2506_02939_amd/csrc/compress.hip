@@ -321,11 +321,11 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     constexpr int CLOADS = GB * CPS / NT;   // chunks of C per thread per stage
     constexpr int CBUF = GB * RS;        // chunks per C buffer
     constexpr int XSLOT = TT * 256;      // chunks per X slot (TT fragments of 32 rows x 8 chunks)
-    constexpr int D = 4;                 // X ring depth in registers (super-steps)
+    constexpr int D = TG == 8 ? 3 : 4;   // X ring depth in registers (super-steps); 128 accumulator registers leave room for 3
     constexpr int UN = SS > D ? SS : D;  // super-steps per unrolled body: a multiple of SS and of D
-    // Stages of C in flight in registers.  Short stages (TG >= 4: one or two super-steps) are over before a load from
-    // L2 has come back, so their loads are issued two stages ahead; the register slot of a stage is its parity,
-    // which is static when the unrolled body holds an even number of stages.
+    // Stages of C in flight in registers, PD of them.  Short stages (one or two super-steps) are over before a load
+    // from L2 has come back, so two are in flight where the registers allow; the register slot of a stage is its
+    // parity, which is static when the unrolled body holds an even number of stages.
     constexpr int PD = (UN / SS) % 2 == 0 ? 2 : 1;
     static_assert(GB * CPS % NT == 0, "stage does not divide over the threads");
 
@@ -451,10 +451,11 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     };
 
     load_c(0, 0);
-    if (PD == 2) load_c(1, 1);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
     store_c(0, 0);
+#pragma unroll
+    for (int d = 1; d <= PD; ++d) load_c(d, d % PD);        // stage d travels in register slot d % PD
     stash_x(xr[0], 0, true);
     __syncthreads();
 
@@ -464,34 +465,52 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
 #pragma unroll
         for (int p = 0; p < UN; ++p) {
             const int gs = bi * UN + p;                      // super-step
-            if (p % SS == 0) {                               // a stage of C begins: its register slot is free again
-                stage = gs / SS;
-                load_c(stage + PD, (p / SS) % PD);           // issued on every path, so that waits stay counted, not full
-            }
+            if (p % SS == 0) stage = gs / SS;                // a stage of C begins
             load_x(xr[(p + D - 1) % D], gs + D - 1);
             stash_x(xr[(p + 1) % D], (gs + 1) & 1, gs + 1 < nss);      // next super-step's tokens into the other slot
             if (gs < nss) {                                  // uniform; only false in the tail of the last body
                 const u32x4_t* cbuf = lds_c + buf * CBUF;
                 const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
-                u32x4_t a[2][TG], bx[2][TT];
-                auto fetch = [&](int u, int which) {
+                // The 4 TG generator fragments of the super-step (MFMA step u, fragment tg: number u TG + tg) are
+                // taken in groups of at most four.  The LDS reads of group q+1 are issued before the MFMAs of group q,
+                // and the scheduling barriers keep that order: left alone, the compiler pulls every read down to its
+                // MFMA to save registers and each MFMA then waits out a full LDS latency.
+                constexpr int GRP = TG < 4 ? TG : 4, NGRP = 4 * TG / GRP;
+                u32x4_t a[2][GRP], bx[2][TT];
+                auto fetch_a = [&](int grp, int which) {
 #pragma unroll
-                    for (int tg = 0; tg < TG; ++tg) a[which][tg] = cbuf[(32 * tg + r) * RS + (p % SS) * 8 + 4 * g + u];
+                    for (int i = 0; i < GRP; ++i) {
+                        const int t = grp * GRP + i, u = t / TG, tg = t % TG;
+                        a[which][i] = cbuf[(32 * tg + r) * RS + (p % SS) * 8 + 4 * g + u];
+                    }
+                };
+                auto fetch_b = [&](int u, int which) {
 #pragma unroll
                     for (int tt = 0; tt < TT; ++tt) bx[which][tt] = xbuf[tt * 256 + r * 8 + ((4 * g + u) ^ (r & 7))];
                 };
-                fetch(0, 0);
+                fetch_b(0, 0);
+                fetch_a(0, 0);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (u < 3) fetch(u + 1, (u + 1) & 1);
+                for (int grp = 0; grp < NGRP; ++grp) {
+                    const int u = grp * GRP / TG;
+                    if (grp + 1 < NGRP) {
+                        const int un = (grp + 1) * GRP / TG;
+                        if (un != u) fetch_b(un, un & 1);
+                        fetch_a(grp + 1, (grp + 1) & 1);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int tg = 0; tg < TG; ++tg)
+                    for (int i = 0; i < GRP; ++i)
 #pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) TR::mma(a[u & 1][tg], bx[u & 1][tt], acc[tg][tt]);
+                        for (int tt = 0; tt < TT; ++tt) TR::mma(a[grp & 1][i], bx[u & 1][tt], acc[(grp * GRP + i) % TG][tt]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (p % SS == SS - 1) {                          // the stage ends: publish the next one
                 if (stage + 1 < nstages) store_c(buf ^ 1, (p / SS + 1) % PD);
+                // the slot is free again: the loads of stage + 1 + PD go out before the barrier and have the barrier
+                // and PD whole stages to come back (issued on every path, so that waits stay counted, not full)
+                load_c(stage + 1 + PD, (p / SS + 1) % PD);
                 __syncthreads();
                 buf ^= 1;
             } else {
