@@ -623,7 +623,7 @@ __global__ __launch_bounds__(256) void k_piece_sum(const float* __restrict__ par
 // ------------------------------------------------------------------------------------------------
 // k_prep: puts both operands of C^T Btilde into the layout the MFMA wants, generator index contiguous:
 //   Bt[c][j] = Btilde_j[c] = sum of generator j's pieces (rounded once to bf16 for bf16 inputs), Ct[l][j] = C_j[l],
-// rows padded with zeros to KP generators (a multiple of 16).  A workgroup transposes a tile of 64 columns x 16
+// rows padded with zeros to KP generators (a multiple of 32: whole stages of k_ctb).  A workgroup transposes a tile of 64 columns x 16
 // generators through LDS: reads run along the columns (coalesced), writes are whole 16-byte chunks.
 template <typename TR> struct PrepIo;
 template <> struct PrepIo<Bf16> {
@@ -722,10 +722,10 @@ __global__ __launch_bounds__(256) void k_prep(const void* __restrict__ C, const 
 // k_ctb: dW (n x m) = C^T (n x k) * Btilde (k x m).  Both operands come from k_prep with the generator index
 // contiguous (Ct[l][j], Bt[c][j]).  Workgroup tile 128 x 128, 4 waves of 64 x 64; the generator index is walked in
 // stages of BK = 4 chunks per row (32 bf16 / 16 fp32: 40 KiB of LDS per workgroup, so three workgroups share a CU;
-// the kernel is bound by latencies, not by LDS or MFMA throughput, and eight-chunk stages with two workgroups per
-// CU measured 13 % slower at k = 1024), staged through LDS with coalesced loads, double buffered, one barrier per stage.  LDS rows are BK+1 chunks apart, which makes the
-// 16-byte reads of a fragment (32 rows, one chunk column) free of bank conflicts.  MFMA step u of a stage takes
-// chunk 2u+g from lane group g, for both operands alike.
+// eight-chunk stages with two workgroups per CU measured the same at k = 1024 and slower at k = 256), staged through
+// LDS with coalesced loads that are issued two stages ahead, double buffered in LDS, one barrier per stage.  LDS rows
+// are BK+1 chunks apart, which makes the 16-byte reads of a fragment (32 rows, one chunk column) free of bank
+// conflicts.  MFMA step u of a stage takes chunk 2u+g from lane group g, for both operands alike.
 //
 // Tile order: workgroups are handed to the 8 XCDs round-robin, and every XCD has its own L2.  Workgroup number
 // bid therefore takes tile (bid % 8) * ceil(T/8) + bid / 8 of an order that walks the output in strips 8 tiles
@@ -763,17 +763,20 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
         src[i] = Ct + size_t(min(l0 + sub + SUBS * i, n - 1)) * KC;
         src[NI + i] = Bt + size_t(min(c0 + sub + SUBS * i, m - 1)) * KC;
     }
-    u32x4_t reg[2 * NI];
-    auto gload = [&](int stage) {
-        const int c = stage * BK + chunk;
-        const uint32_t keep = c < KC ? 0xffffffffu : 0u;       // chunks past the last generator count as zeros
-        const int cc = min(c, KC - 1);
+    // Two stages travel in registers (stage s in slot s % 2), so that a load has two stages of MFMAs to come back.
+    // Rows hold a whole number of stages (k_prep pads with zero generators), so nothing is masked: a mask on the
+    // loaded value makes the compiler wait for the load right where it is issued.  Stages past the last one re-read
+    // the last one and are never stored.
+    const int nst = KC / BK;
+    u32x4_t reg[2][2 * NI];
+    auto gload = [&](int stage, int slot) {
+        const int c = min(stage, nst - 1) * BK + chunk;
 #pragma unroll
-        for (int i = 0; i < 2 * NI; ++i) reg[i] = src[i][cc] & keep;
+        for (int i = 0; i < 2 * NI; ++i) reg[slot][i] = src[i][c];
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int buf, int slot) {
 #pragma unroll
-        for (int i = 0; i < 2 * NI; ++i) lds[buf][(i < NI ? 0 : TILE) + (sub + SUBS * (i % NI)) * RS + chunk] = reg[i];
+        for (int i = 0; i < 2 * NI; ++i) lds[buf][(i < NI ? 0 : TILE) + (sub + SUBS * (i % NI)) * RS + chunk] = reg[slot][i];
     };
 
     f32x16_t acc[2][2];
@@ -784,26 +787,34 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][bq][i] = 0.f;
 
-    const int nst = (KC + BK - 1) / BK;
-    gload(0);
-    sstore(0);
+    gload(0, 0);
+    gload(1, 1);
+    sstore(0, 0);
+    gload(2, 0);
     __syncthreads();
-    for (int st = 0; st < nst; ++st) {
-        if (st + 1 < nst) gload(st + 1);
-        const u32x4_t* A = lds[st & 1] + (wy * 64 + r) * RS + g;
-        const u32x4_t* B = lds[st & 1] + TILE + (wx * 64 + r) * RS + g;
+    for (int st = 0; st < nst; st += 2) {
 #pragma unroll
-        for (int u = 0; u < BK / 2; ++u) {
-            u32x4_t a[2], bq[2];
+        for (int h = 0; h < 2; ++h) {                  // stage st + h: LDS buffer h, register slot h
+            const int cur = st + h;
+            if (cur < nst) {                           // uniform; false only for the second half of an odd last pair
+                const u32x4_t* A = lds[h] + (wy * 64 + r) * RS + g;
+                const u32x4_t* B = lds[h] + TILE + (wx * 64 + r) * RS + g;
+                u32x4_t a[BK / 2][2], bq[BK / 2][2];
 #pragma unroll
-            for (int q = 0; q < 2; ++q) { a[q] = A[32 * q * RS + 2 * u]; bq[q] = B[32 * q * RS + 2 * u]; }
+                for (int u = 0; u < BK / 2; ++u)
 #pragma unroll
-            for (int fa = 0; fa < 2; ++fa)
+                    for (int q = 0; q < 2; ++q) { a[u][q] = A[32 * q * RS + 2 * u]; bq[u][q] = B[32 * q * RS + 2 * u]; }
 #pragma unroll
-                for (int fb = 0; fb < 2; ++fb) TR::mma(a[fa], bq[fb], acc[fa][fb]);
+                for (int u = 0; u < BK / 2; ++u)
+#pragma unroll
+                    for (int fa = 0; fa < 2; ++fa)
+#pragma unroll
+                        for (int fb = 0; fb < 2; ++fb) TR::mma(a[u][fa], bq[u][fb], acc[fa][fb]);
+            }
+            if (cur + 1 < nst) sstore(h ^ 1, h ^ 1);
+            gload(cur + 3, h ^ 1);                     // the slot is free again
+            __syncthreads();
         }
-        if (st + 1 < nst) sstore((st + 1) & 1);
-        __syncthreads();
     }
 
     // D layout of the 32x32 MFMA: register i of lane (r,g) is row 8*(i/4)+4*g+(i%4), column r: one store
