@@ -623,7 +623,7 @@ __global__ __launch_bounds__(256) void k_piece_sum(const float* __restrict__ par
 // ------------------------------------------------------------------------------------------------
 // k_prep: puts both operands of C^T Btilde into the layout the MFMA wants, generator index contiguous:
 //   Bt[c][j] = Btilde_j[c] = sum of generator j's pieces (rounded once to bf16 for bf16 inputs), Ct[l][j] = C_j[l],
-// rows padded with zeros to KP generators (a multiple of 32: whole stages of k_ctb).  A workgroup transposes a tile of 64 columns x 16
+// rows padded with zeros to KP generators (whole stages of k_ctb: a multiple of 32 for bf16, 16 for fp32).  A workgroup transposes a tile of 64 columns x 16
 // generators through LDS: reads run along the columns (coalesced), writes are whole 16-byte chunks.
 template <typename TR> struct PrepIo;
 template <> struct PrepIo<Bf16> {

@@ -94,7 +94,7 @@ struct GradPlan {
     int sort_one_rows;    // batches up to this many rows are sorted by one workgroup in one kernel
     int wave_groups;      // W: 512-column groups per wave (1..3); a workgroup of 4 waves covers 4*W groups of a row
     int wg_cols;          // workgroups side by side along a row: ceil(col_groups / (4*W))
-    int64_t kpad;         // k rounded up to a multiple of 32 (a whole number of k_ctb stages for both element types)
+    int64_t kpad;         // k rounded up to a whole number of k_ctb stages (32 generators for bf16, 16 for fp32)
     int slice_rows;       // rows per slice of the counting sort (1024 or 4096)
     int64_t nslices;      // ceil(b / slice_rows)
     size_t off_list, off_hdr, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
@@ -129,7 +129,8 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
         p->chunks = (even > longest ? even : longest) + 1;
     }
     p->nslots = p->chunks + k;
-    p->kpad = (k + 31) / 32 * 32;
+    const int64_t stage_gens = 4 * per_chunk(dt);      // generators per k_ctb stage: 32 (bf16) or 16 (fp32)
+    p->kpad = (k + stage_gens - 1) / stage_gens * stage_gens;
     // Counting sort of the rows by generator: short slices spread the scattered list writes over many CUs, but every
     // slice's workgroup sums the whole table of slice histograms (slices x k entries), so that table must stay small.
     p->slice_rows = ((b + 1023) / 1024) * k <= 4096 ? 1024 : 4096;
