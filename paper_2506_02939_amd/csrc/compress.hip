@@ -433,10 +433,11 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     // registers -> this wave's LDS tile; `fresh` (uniform): the window has not been stashed before, so with a finite
     // tolerance its squares are added to the row norms (every chunk of X passes here exactly once)
     auto stash_x = [&](const u32x4_t (&src)[TT][4], int slot, bool fresh) {
+        const uint32_t live = fresh ? 0xffffffffu : 0u;      // windows past the end of the walk enter as zeros
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lds_x[slot * XSLOT + tt * 256 + i * 64 + lane] = src[tt][i];
+            for (int i = 0; i < 4; ++i) lds_x[slot * XSLOT + tt * 256 + i * 64 + lane] = src[tt][i] & live;
         if (want_norm && fresh) {
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
@@ -466,9 +467,24 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         for (int p = 0; p < UN; ++p) {
             const int gs = bi * UN + p;                      // super-step
             if (p % SS == 0) stage = gs / SS;                // a stage of C begins
-            load_x(xr[(p + D - 1) % D], gs + D - 1);
-            stash_x(xr[(p + 1) % D], (gs + 1) & 1, gs + 1 < nss);      // next super-step's tokens into the other slot
-            if (gs < nss) {                                  // uniform; only false in the tail of the last body
+            // What a super-step does besides its MFMAs, in three parts that are placed between the MFMA groups so that
+            // their issue slots and waits hide behind matrix work (a wave issues in order; an MFMA keeps the matrix
+            // pipe busy for 32 cycles during which the wave's next instructions of other kinds go out):
+            auto side = [&](int part) {
+                if (part == 0) load_x(xr[(p + D - 1) % D], gs + D - 1);
+                if (part == 1) stash_x(xr[(p + 1) % D], (gs + 1) & 1, gs + 1 < nss);   // next super-step's tokens, other slot
+                if (part == 2 && p % SS == SS - 1) {         // the stage ends: fill the C buffer nobody reads now
+                    // (also past the last stage, with the last window again: the MFMAs of the tail multiply what
+                    // this buffer holds by zeros, so it must hold finite numbers)
+                    store_c(buf ^ 1, (p / SS + 1) % PD);
+                    // the slot is free again: the loads of stage + 1 + PD have the barrier and PD whole stages to
+                    // come back (issued on every path, so that waits stay counted, not full)
+                    load_c(stage + 1 + PD, (p / SS + 1) % PD);
+                }
+            };
+            constexpr bool RIDE = TG < 8;       // with 128 accumulator registers the longer live ranges would spill
+            if (!RIDE) { side(0); side(1); side(2); }
+            {   // (in the tail of the last body the walk is over: its windows were stashed as zeros and add nothing)
                 const u32x4_t* cbuf = lds_c + buf * CBUF;
                 const u32x4_t* xbuf = lds_x + (gs & 1) * XSLOT;
                 // The 4 TG generator fragments of the super-step (MFMA step u, fragment tg: number u TG + tg) are
@@ -476,6 +492,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 // and the scheduling barriers keep that order: left alone, the compiler pulls every read down to its
                 // MFMA to save registers and each MFMA then waits out a full LDS latency.
                 constexpr int GRP = TG < 4 ? TG : 4, NGRP = 4 * TG / GRP;
+                constexpr int S1 = NGRP / 4 > 1 ? NGRP / 4 : 1, S2 = NGRP / 2 > 2 ? NGRP / 2 : 2;   // groups the parts follow
                 u32x4_t a[2][GRP], bx[2][TT];
                 auto fetch_a = [&](int grp, int which) {
 #pragma unroll
@@ -503,14 +520,13 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                     for (int i = 0; i < GRP; ++i)
 #pragma unroll
                         for (int tt = 0; tt < TT; ++tt) TR::mma(a[grp & 1][i], bx[u & 1][tt], acc[(grp * GRP + i) % TG][tt]);
+                    if (RIDE && grp == 0) side(0);
+                    if (RIDE && grp == S1) side(1);
+                    if (RIDE && grp == S2) side(2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (p % SS == SS - 1) {                          // the stage ends: publish the next one
-                if (stage + 1 < nstages) store_c(buf ^ 1, (p / SS + 1) % PD);
-                // the slot is free again: the loads of stage + 1 + PD go out before the barrier and have the barrier
-                // and PD whole stages to come back (issued on every path, so that waits stay counted, not full)
-                load_c(stage + 1 + PD, (p / SS + 1) % PD);
                 __syncthreads();
                 buf ^= 1;
             } else {
