@@ -822,19 +822,31 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
     // library, and as ordinary stores its dirty lines are written back later, in the middle of the next kernels'
     // streams (measured: 25 % slower k_contract and k_score at the 7B-shaped layer).
     const int lw = l0 + wy * 64, cw = c0 + wx * 64;
+    const bool inside = l0 + 128 <= n && c0 + 128 <= m;      // uniform: a tile away from the edges stores unguarded
     if constexpr (!OUT16) {
         float* __restrict__ dW = static_cast<float*>(dWv);
+        if (inside) {
+            float* __restrict__ base = dW + size_t(lw + 4 * g) * m + cw + r;
 #pragma unroll
-        for (int fa = 0; fa < 2; ++fa)
+            for (int fa = 0; fa < 2; ++fa)
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) {
-                const int c = cw + 32 * fb + r;
+                for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
-                    if (l < n && c < m) __builtin_nontemporal_store(acc[fa][fb][i], &dW[size_t(l) * m + c]);
+                    for (int i = 0; i < 16; ++i)
+                        __builtin_nontemporal_store(acc[fa][fb][i], base + size_t(32 * fa + 8 * (i >> 2) + (i & 3)) * m + 32 * fb);
+        } else {
+#pragma unroll
+            for (int fa = 0; fa < 2; ++fa)
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb) {
+                    const int c = cw + 32 * fb + r;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
+                        if (l < n && c < m) __builtin_nontemporal_store(acc[fa][fb][i], &dW[size_t(l) * m + c]);
+                    }
                 }
-            }
+        }
     } else {
         // even lane: keeps rows +0,+1 of each group of four and gets its neighbour's values of those rows (the column
         // to its right); odd lane: keeps rows +2,+3 and gets the column to its left.  m is even, so a pair never
