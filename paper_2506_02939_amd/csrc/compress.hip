@@ -3,7 +3,8 @@
 // final decision drops the rows whose best representative is outside the neighbourhood.
 //
 // Launches on the caller's stream:
-//   k_gather    C_j = X[idx_j] (bit copy), ||C_j||^2 in fp64, a content hash per generator
+//   k_gather    C_j = X[idx_j] (bit copy), ||C_j||^2 in fp64, a content hash per generator (k_gather_arg: the same
+//               with up to 512 sampled row numbers in the kernel's argument block)
 //   k_score     streams X once; D = C X^T on the matrix cores with C staged through LDS, then per token the
 //               largest values of s(i,j) = <X_i,C_j>^2/||C_j||^2 (Lemma 1) and where they occur.  With up to 256
 //               generators (one column block) it also takes the final decision: f, alpha (Eq. 1), the few rows
@@ -302,8 +303,9 @@ __device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const
 // the MFMA layout (lane r needs 16 bytes of row r).  Inside the tile, row r keeps chunk c at position c^(r&7),
 // which makes both the lane-linear writes and the column reads free of bank conflicts.
 // C: staged through LDS in stages of 64/TG chunks per generator (32 KiB per stage), double buffered; the
-// global loads of stage s+1 are in flight while stage s is consumed.
-// LDS fragments for MFMA step u+1 are requested before the MFMAs of step u are issued.
+// global loads of the next one or two stages are in flight in registers while a stage is consumed.
+// The generator fragments of a super-step are read from LDS one group of up to four ahead of their MFMAs, and the
+// loads, stashes and stage stores of the super-step are placed between those groups.
 // FUSED (one column block holds every generator): the epilogue takes the final decision itself and writes f and
 // alpha; otherwise it writes one candidate record per token and column block for k_finalize.
 template <typename TR, int TG, int TT, int NW, bool ALIGNED, bool FUSED>
