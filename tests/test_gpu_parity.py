@@ -132,6 +132,9 @@ SMALL = [
     # long rows: 256 windows of the hidden dimension per row in k_score, 33 column groups in k_contract
     ("bf16_long_rows", "llama7b_k32", dict(seqs=1, seq_len=300, n=16384, m=16392, k=5, centres=8)),
     ("f32_long_rows", "tiny", dict(seqs=1, seq_len=130, n=8196, m=4100, k=3, centres=5)),
+    # the largest k the library takes, with every row a generator (k = b): 64 column blocks in k_score, one grouping
+    # workgroup per generator, the pinned index ring; the padding rows of the recipe are bit-identical generators
+    ("bf16_k16384_every_row_a_generator", "llama60m", dict(seqs=4, seq_len=4096, n=16, m=24, k=16384, centres=64)),
 ]
 
 
