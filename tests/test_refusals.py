@@ -1,4 +1,4 @@
-"""Refusals that need no GPU: bench.py on more than one GPU or without a GPU, and the binding without its library.
+"""Refusals that need no GPU: bench.py on more than one GPU or without a GPU, and the binding without its library."""
 import os
 import subprocess
 import sys
