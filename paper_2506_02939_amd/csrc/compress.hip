@@ -647,7 +647,8 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         }
         const Neighbourhood nb{keep, &drop_count};
         if (FUSED) {
-            decide_or_queue(inv, cn2, hash, g == 0 && row < b, row, best, nx, nb, f, alpha, &redo_count, redo_entries);
+            // (one column block: generator j's 1/||C_j||^2 sits in lds_inv[j], no need to go to memory for it)
+            decide_or_queue(lds_inv, cn2, hash, g == 0 && row < b, row, best, nx, nb, f, alpha, &redo_count, redo_entries);
         } else {
             if (g == 0 && row < b) {
                 u32x4_t* rec = cand + (size_t(row) * ncb + cb) * 2;
