@@ -4,11 +4,11 @@
  * The two calls follow the paper's statement of the method (Sec. 3.2): approximate
  * O = A^T B for A in R^{b x n}, B in R^{b x m} in two stages,
  *
- *   pamm_compress   "Compressing A": choose k generator rows C, and for every row A_i
+ *   pamm_compress   first stage (compression of A): choose k generator rows C, and for every row A_i
  *                   the generator f(i) whose line gives the smallest projection residual
  *                   together with the coefficient alpha_i = <A_i,C_f(i)>/||C_f(i)||^2
  *                   (Eq. 1, Lemma 1; Alg. 1, procedure Compress, at eps = infinity);
- *   pamm_grad       "Approximate Matrix Multiplication": Btilde_j = sum_{i: f(i)=j} alpha_i B_i,
+ *   pamm_grad       second stage (the approximate product): Btilde_j = sum_{i: f(i)=j} alpha_i B_i,
  *                   O~ = C^T Btilde  (Alg. 1, procedure ApproxMM).
  *
  * In training, A is the saved input X of the fused Q|K|V projection, B is dY = [dQ|dK|dV]
@@ -28,9 +28,9 @@
  *     stream).  The calls do not synchronise the stream: outputs are valid once the
  *     stream has reached the end of the enqueued work.  Scratch memory comes from the
  *     caller through (ws, ws_bytes), sized by the *_workspace queries; the compute
- *     calls allocate no device memory.  (Up to 512 sampled indices travel in a kernel's
- *     argument block; for larger k pamm_compress keeps a small pinned host ring for them,
- *     created on first use per device.)
+ *     calls allocate nothing, take no lock and never block.  (Sampled indices travel in
+ *     kernel argument blocks, 512 per launch, so a captured launch replays with the
+ *     indices it was captured with.)
  *   - Errors are return codes.  All argument checks happen on the host before
  *     anything is enqueued; on a non-OK return nothing was enqueued and no output
  *     was touched, except PAMM_ERR_DEVICE (a HIP call failed part-way).
@@ -75,7 +75,7 @@ size_t pamm_compress_workspace(int64_t b, int64_t n, int64_t k, pamm_dtype dt);
 size_t pamm_grad_workspace(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt);
 
 /*
- * Alg. 1, Compress, "sample indices I subset [b] uniformly without replacement, |I| = k".
+ * Alg. 1, Compress, sampling step: k distinct row numbers, every k-subset equally likely.
  * The paper fixes only the distribution; this library fixes the stream as: splitmix64
  * seeded with `seed`; draw t = 0..k-1 takes r = t + u where u is uniform on [0, b-t)
  * by rejection on the 64-bit output (reject x < 2^64 mod (b-t), u = x mod (b-t));
@@ -89,7 +89,7 @@ pamm_status pamm_sample_indices(int64_t b, int64_t k, uint64_t seed, int32_t *id
  * Alg. 1, procedure Compress, with eps = infinity (no row dropped, beta = 1).
  *   X      in   b x n, dtype dt
  *   seed   in   selects the generators through pamm_sample_indices(b, k, seed)
- *   C      out  k x n, dtype dt: C_j = X[idx_j], bit copies                     ("C <- A[I,:]")
+ *   C      out  k x n, dtype dt: C_j = X[idx_j], bit copies                     (Alg. 1, generator rows)
  *   f      out  b int32: f(i) = lowest j maximising <X_i,C_j>^2/||C_j||^2       (Lemma 1: argmax |csim|)
  *   alpha  out  b fp32:  alpha_i = <X_i,C_f(i)>/||C_f(i)||^2                    (Eq. 1)
  * A generator with zero norm scores 0 and yields alpha 0; a zero row gets f = 0, alpha = 0.
@@ -102,8 +102,8 @@ pamm_status pamm_compress(const void *X, int64_t b, int64_t n, int64_t k, uint64
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
- * The same with caller-chosen generators ("these can be any points close enough to the
- * points in A", Sec. 3.2; also the hook tests use to bypass the sampler).
+ * The same with caller-chosen generators (Sec. 3.2 allows any set of representative rows;
+ * also the hook tests use to bypass the sampler).
  *   idx_dev  in  DEVICE pointer to k int32 row numbers in [0,b); duplicates are allowed
  *                (the lowest j of identical generators wins).  Values outside [0,b) are
  *                clamped into range by the kernel rather than faulting.
@@ -116,7 +116,7 @@ pamm_status pamm_compress_idx(const void *X, int64_t b, int64_t n, int64_t k, co
  * Alg. 1, procedure Compress, with a finite tolerance eps >= 0: the neighbourhood condition of Eq. 2,
  *   ||X_i - alpha_i C_f(i)||_2 <= eps ||X_i||_2,
  * is applied to the representative of every row; a row that fails it is dropped, i.e. its alpha is set to 0 (its
- * f stays: "alpha[e > eps] <- 0").  Eq. 2 (relative to ||X_i||) is taken where Alg. 1 prints the absolute e > eps.
+ * f stays: Alg. 1 only zeroes alpha).  Eq. 2 (relative to ||X_i||) is taken where Alg. 1 prints the absolute e > eps.
  * eps = 0 keeps only rows lying exactly on a generator's line: uniform column-row sampling (Sec. 4.1).
  * eps >= 1 (or +infinity) can drop nothing and is the same as pamm_compress.  Negative or NaN: PAMM_ERR_INVALID_ARG.
  *   eta    out  DEVICE pointer to one int32 (4-byte aligned): the number of rows dropped.  The normalisation factor
@@ -137,8 +137,8 @@ pamm_status pamm_compress_idx_eps(const void *X, int64_t b, int64_t n, int64_t k
  *   C      in   k x n, dtype dt          f      in  b int32 in [0,k)        alpha  in  b fp32
  *   dY     in   b x m, dtype dt
  *   dW     out  n x m fp32, overwritten
- * Rows are grouped by f with a stable counting sort and summed in fp32 in a fixed order, so
- * the result is bit-reproducible from call to call.  Rows with alpha_i = 0 add nothing and are
+ * Rows are grouped by f with a stable counting sort (rows of one generator stay in increasing
+ * order) and summed in fp32 in that order, so the result is bit-reproducible from call to call.  Rows with alpha_i = 0 add nothing and are
  * left out: their rows of dY are never read.  For PAMM_BF16 the contracted rows are
  * rounded to bf16 once before the C^T Btilde product (fp32 accumulation); for PAMM_F32 the
  * product is carried out in fp32 throughout.  Entries of f outside [0,k) are clamped into
@@ -195,6 +195,30 @@ pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
 pamm_status pamm_profile_begin(void);
 pamm_status pamm_profile_end(double *ms_total, int64_t *launches);
 const char *pamm_kernel_name(int id);
+
+/*
+ * Test hooks (host-only, process-wide, not thread-safe; no product call needs them).
+ *
+ * pamm_debug_set_plan overrides the launch heuristics of the calls above so that tests can run the kernel variants
+ * and grid decompositions the heuristics do not pick at small shapes; a field that is 0 or out of its range leaves
+ * the heuristic in charge, NULL clears every override.  The overrides also enter the *_workspace queries, so query
+ * the workspace after setting them.
+ *   score_tg       32-generator fragments per wave of the score kernel: 1, 2, 4 or 8 (at most what k allows)
+ *   score_nw       waves per workgroup of the score kernel: 2, 4 or 8
+ *   piece_rows     positions of the sorted list per chunk of the contraction: a multiple of 16 in [16, 4096]
+ *   contract_w     512-column groups per wave of the contraction: 1, 2 or 3
+ *   sort_one_rows  largest b grouped by the single-workgroup counting sort: 1..16384
+ *
+ * pamm_debug_bounded writes `count` consecutive draws of the sampler's bounded step (uniform on [0, range) by
+ * rejection, as specified at pamm_sample_indices) from one generator seeded with `seed` into out_host, so that a
+ * test can drive the rejection branch with ranges near 2^63, which the sampler itself (range < 2^31) takes with
+ * probability below 2^-33.  range = 0 or out_host = NULL: PAMM_ERR_INVALID_ARG.
+ */
+typedef struct {
+    int score_tg, score_nw, piece_rows, contract_w, sort_one_rows;
+} pamm_debug_plan;
+pamm_status pamm_debug_set_plan(const pamm_debug_plan *plan_host);
+pamm_status pamm_debug_bounded(uint64_t seed, uint64_t range, int64_t count, uint64_t *out_host);
 
 #ifdef __cplusplus
 }

@@ -10,7 +10,7 @@
  * Algorithm 1; the tolerance eps may be infinite, in which case no row is ever
  * dropped and the normalisation factor beta is 1):
  *
- *   Compress(A, k):   I   = k row indices, uniform without replacement   (Alg. 1, Compress, "Sample indices")
+ *   Compress(A, k):   I   = k row indices, uniform without replacement   (Alg. 1, Compress, sampling step)
  *                     C_j = A[I_j, :]                                     (Alg. 1, generators)
  *                     alpha(i,j) = <A_i, C_j> / ||C_j||^2                 (Eq. 1)
  *                     f(i) = argmin_j ||A_i - alpha(i,j) C_j||_2
@@ -18,9 +18,9 @@
  *                     alpha_i = alpha(i, f(i))
  *                     e_i = ||A_i - alpha_i C_f(i)||_2 ;  alpha_i <- 0 where
  *                     e_i > eps ||A_i||_2                                 (Eq. 2, neighbourhood condition)
- *                     eta = number of rows dropped, beta = b / (b - eta)  (Sec. 3.2, "Normalization factor beta")
+ *                     eta = number of rows dropped, beta = b / (b - eta)  (Sec. 3.2, paragraph on the normalisation factor)
  *   ApproxMM(C, alpha, f, B):
- *                     Btilde_j = sum_{i : f(i) = j} alpha_i B_i           (Sec. 3.2, "Approximate Matrix Multiplication")
+ *                     Btilde_j = sum_{i : f(i) = j} alpha_i B_i           (Sec. 3.2, second stage: the approximate product)
  *                     Otilde   = beta C^T Btilde                          (Alg. 1, ApproxMM; beta as above)
  *
  * Readings taken where the paper is silent or inconsistent:
@@ -37,16 +37,17 @@
  *     Eq. 2 (relative) is taken.  A dropped row keeps its f (Alg. 1 only zeroes
  *     alpha).  If every row is dropped beta is undefined in the paper; 0 here,
  *     so that Otilde = 0.
- *   - the sampler is specified, because the paper only says "uniformly without
- *     replacement": splitmix64 seeded with `seed`; draw t (t = 0..k-1) takes
+ *   - the sampler is specified, because the paper fixes only the distribution
+ *     (uniform over the k-subsets, no index twice): splitmix64 seeded with `seed`; draw t (t = 0..k-1) takes
  *     r = t + bounded(b - t) where bounded(u) is unbiased rejection sampling
  *     on the 64-bit output (reject x < 2^64 mod u, return x mod u); textbook
  *     Fisher-Yates swap of positions t and r of the identity array; generator
  *     j is the j-th draw (draw order, not sorted).
  *
  * Parity pins (tests/test_oracle_*.py, none of which re-use this code):
- *   sampler      splitmix64 published vectors; permutation at k = b; uniformity chi^2.
- *                The index stream for a given seed is fixed by the specification
+ *   sampler      splitmix64 published vectors; permutation at k = b; uniformity chi^2; the bounded
+ *                draw, rejection branch included, against exact integer arithmetic on ranges
+ *                just above 2^63.  The index stream for a given seed is fixed by the specification
  *                above only: "parity unpinned" by the paper.
  *   f            brute-force argmin of the true residual on tiny inputs (numpy).
  *   alpha        orthogonality of the residual to C_f(i); Pythagoras; alpha = 1 on generators.
@@ -135,6 +136,17 @@ static uint64_t bounded(uint64_t *state, uint64_t u)
     return x % u;
 }
 
+/* `count` consecutive bounded(u) draws from a generator seeded with `seed`, exported so that a test can drive the
+   rejection branch (ranges just above 2^63 reject about every second output; the ranges the sampler itself uses,
+   below 2^31, reject with probability under 2^-33).  Returns 0, or -1 on bad arguments. */
+int pamm_oracle_bounded(uint64_t seed, uint64_t u, int64_t count, uint64_t *out)
+{
+    if (u == 0 || count < 0 || !out) return -1;
+    uint64_t st = seed;
+    for (int64_t i = 0; i < count; ++i) out[i] = bounded(&st, u);
+    return 0;
+}
+
 /* k distinct indices of [0,b), uniform without replacement, in draw order.  Returns 0, or -1 on bad arguments. */
 int pamm_oracle_sample(int64_t b, int64_t k, uint64_t seed, int32_t *idx)
 {
@@ -158,7 +170,7 @@ int pamm_oracle_sample(int64_t b, int64_t k, uint64_t seed, int32_t *idx)
 
 /*
  * Inputs : A (b x n, element type dtype), idx[k] (generator rows).
- * Outputs: C      k x n doubles, C_j = A[idx_j]          (Alg. 1, "C <- A[I,:]")
+ * Outputs: C      k x n doubles, C_j = A[idx_j]          (Alg. 1, Compress, generator rows)
  *          f      b int32,  0-based assignment            (Lemma 1, lowest j on ties)
  *          alpha  b doubles                               (Eq. 1 at j = f(i))
  *          best   b doubles: s(i, f(i))                   } diagnostics that let a test apply the
@@ -300,21 +312,4 @@ int pamm_oracle_grad(const double *C, const int32_t *f, const double *alpha,
         for (int64_t c = 0; c < m; ++c) out[c] *= beta;
     }
     return 0;
-}
-
-/*
- * One score s(i,j) = <A_i, C_j>^2 / ||C_j||^2 for a caller-chosen pair, with C_j = A[row_j].
- * Lets a test look at single entries of the b x k score table at sizes where the
- * whole table is not wanted.
- */
-double pamm_oracle_score(const void *A, int dtype, int64_t n, int64_t i, int64_t row_j)
-{
-    double d = 0.0, c2 = 0.0;
-    for (int64_t l = 0; l < n; ++l) {
-        double x = decode(A, dtype, (size_t)i * (size_t)n + (size_t)l);
-        double c = decode(A, dtype, (size_t)row_j * (size_t)n + (size_t)l);
-        d += x * c;
-        c2 += c * c;
-    }
-    return (c2 > 0.0) ? (d * d) / c2 : 0.0;
 }

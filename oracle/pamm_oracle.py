@@ -50,8 +50,8 @@ def _load():
         lib.pamm_oracle_beta.restype = ctypes.c_double
         lib.pamm_oracle_grad.argtypes = [f64p, i32p, f64p, vp, ctypes.c_int, i64, i64, i64, i64, ctypes.c_double, f64p, f64p]
         lib.pamm_oracle_grad.restype = ctypes.c_int
-        lib.pamm_oracle_score.argtypes = [vp, ctypes.c_int, i64, i64, i64]
-        lib.pamm_oracle_score.restype = ctypes.c_double
+        lib.pamm_oracle_bounded.argtypes = [ctypes.c_uint64, ctypes.c_uint64, i64, ctypes.POINTER(ctypes.c_uint64)]
+        lib.pamm_oracle_bounded.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -101,6 +101,15 @@ def _p(a, ty):
 def splitmix64(seed: int, count: int) -> np.ndarray:
     out = np.empty(count, dtype=np.uint64)
     _load().pamm_oracle_splitmix64(ctypes.c_uint64(seed), count, _p(out, ctypes.c_uint64))
+    return out
+
+
+def bounded(seed: int, u: int, count: int) -> np.ndarray:
+    """`count` consecutive draws of the sampler's bounded(u) (uniform on [0,u) by rejection) from one seeded generator."""
+    out = np.empty(count, dtype=np.uint64)
+    rc = _load().pamm_oracle_bounded(ctypes.c_uint64(seed & (2**64 - 1)), ctypes.c_uint64(u), count, _p(out, ctypes.c_uint64))
+    if rc != 0:
+        raise ValueError("pamm_oracle_bounded: bad arguments")
     return out
 
 
@@ -173,9 +182,3 @@ def grad(C, f, alpha, dY, beta: float = 1.0):
     if rc != 0:
         raise ValueError("pamm_oracle_grad: bad arguments")
     return Bt, O
-
-
-def score(X, i: int, row_j: int) -> float:
-    """s(i, j) for the generator C_j = X[row_j]."""
-    a, code = as_raw(X)
-    return float(_load().pamm_oracle_score(a.ctypes.data_as(ctypes.c_void_p), code, a.shape[1], int(i), int(row_j)))

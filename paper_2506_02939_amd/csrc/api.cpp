@@ -8,6 +8,7 @@ using namespace pamm;
 
 namespace pamm {
 Profiler g_profiler;
+pamm_debug_plan g_plan_override = {0, 0, 0, 0, 0};
 }
 
 extern "C" const char* pamm_status_string(pamm_status s) {
@@ -71,6 +72,18 @@ extern "C" pamm_status pamm_sample_indices(int64_t b, int64_t k, uint64_t seed, 
         displaced[r] = vt;      // position t is never looked at again, so only r needs recording
         idx_host[t] = int32_t(vr);
     }
+    return PAMM_OK;
+}
+
+extern "C" pamm_status pamm_debug_set_plan(const pamm_debug_plan* plan_host) {
+    g_plan_override = plan_host ? *plan_host : pamm_debug_plan{0, 0, 0, 0, 0};
+    return PAMM_OK;
+}
+
+extern "C" pamm_status pamm_debug_bounded(uint64_t seed, uint64_t range, int64_t count, uint64_t* out_host) {
+    if (!out_host || range == 0 || count < 0) return PAMM_ERR_INVALID_ARG;
+    SplitMix64 rng{seed};
+    for (int64_t i = 0; i < count; ++i) out_host[i] = rng.below(range);
     return PAMM_OK;
 }
 

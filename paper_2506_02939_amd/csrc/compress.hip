@@ -12,9 +12,6 @@
 //   k_finalize  only with more than 256 generators: merges the column blocks and takes that final decision
 #include <hip/hip_runtime.h>
 
-#include <mutex>
-#include <vector>
-
 #include "pamm_device.h"
 #include "pamm_plan.h"
 #include "pamm_profile.h"
@@ -82,17 +79,16 @@ struct Best {
 };
 
 // ------------------------------------------------------------------------------------------------
-// k_gather: one workgroup per generator.  The row numbers come from memory (caller-chosen generators, or more than
-// kArgGenerators sampled ones) or ride in the kernel's own argument block (k_gather_arg): the sampled indices then
-// need no buffer that outlives the call, and a captured launch replays with the indices it was captured with.
+// k_gather: one workgroup per generator.  The row numbers come from memory (caller-chosen generators) or ride in the
+// kernel's own argument block, kArgGenerators per launch (k_gather_arg): sampled indices then need no buffer that
+// outlives the call, and a captured launch replays with the indices it was captured with.
 constexpr int kArgGenerators = 512;
 struct IdxByValue { int32_t v[kArgGenerators]; };
 
 template <typename TR>
-__device__ __forceinline__ void gather_row(const u32x4_t* __restrict__ X, int src, int b, int nch, u32x4_t* __restrict__ C,
+__device__ __forceinline__ void gather_row(const u32x4_t* __restrict__ X, int j, int src, int b, int nch, u32x4_t* __restrict__ C,
                                            int32_t* __restrict__ idx_out, float* __restrict__ inv, double* __restrict__ cn2,
                                            unsigned long long* __restrict__ hash, int32_t* __restrict__ eta) {
-    const int j = blockIdx.x;
     if (eta && j == 0 && threadIdx.x == 0) *eta = 0;          // rows dropped by the neighbourhood condition: counted later
     src = src < 0 ? 0 : (src >= b ? b - 1 : src);
     const u32x4_t* xr = X + size_t(src) * nch;
@@ -134,15 +130,16 @@ __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, c
                                                 u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
                                                 double* __restrict__ cn2, unsigned long long* __restrict__ hash,
                                                 int32_t* __restrict__ eta) {
-    gather_row<TR>(X, idx_in[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
+    gather_row<TR>(X, blockIdx.x, idx_in[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
 }
 
+// generators j0 .. j0 + gridDim.x - 1, their row numbers in the argument block
 template <typename TR>
-__global__ __launch_bounds__(256) void k_gather_arg(const u32x4_t* __restrict__ X, const IdxByValue idx_in, int b, int nch,
+__global__ __launch_bounds__(256) void k_gather_arg(const u32x4_t* __restrict__ X, const IdxByValue idx_in, int j0, int b, int nch,
                                                     u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
                                                     double* __restrict__ cn2, unsigned long long* __restrict__ hash,
                                                     int32_t* __restrict__ eta) {
-    gather_row<TR>(X, idx_in.v[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
+    gather_row<TR>(X, j0 + blockIdx.x, idx_in.v[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -705,8 +702,6 @@ __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X,
 
 // ------------------------------------------------------------------------------------------------ host side
 
-static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
 struct ScoreArgs {
     const void* X; const void* C; const float* inv; const double* cn2; const unsigned long long* hash;
     int b, nch, k;
@@ -749,9 +744,11 @@ static void launch_score(const CompressPlan& pl, const ScoreArgs& a, hipStream_t
     else launch_score_blocks<TR, true>(pl, a, s);
 }
 
+// idx_dev: the generators' row numbers in device memory, or NULL: then idx_host holds them (host memory, only read
+// during the call) and they travel in argument blocks.
 template <typename TR>
-static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, int n, int k, const int32_t* idx_src,
-                                const IdxByValue* idx_arg, double keep, void* C, int32_t* f, float* alpha, int32_t* eta, char* ws,
+static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, int n, int k, const int32_t* idx_dev,
+                                const int32_t* idx_host, double keep, void* C, int32_t* f, float* alpha, int32_t* eta, char* ws,
                                 hipStream_t s) {
     const int nch = n / TR::kPerChunk;
     int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
@@ -762,12 +759,18 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
 
     {
         ScopedSpan span(kGather, s);
-        if (idx_arg)
-            hipLaunchKernelGGL((k_gather_arg<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, *idx_arg, b, nch, (u32x4_t*)C, idx, inv,
-                               cn2, hash, eta);
-        else
-            hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_src, b, nch, (u32x4_t*)C, idx, inv, cn2,
+        if (idx_dev) {
+            hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_dev, b, nch, (u32x4_t*)C, idx, inv, cn2,
                                hash, eta);
+        } else {
+            for (int j0 = 0; j0 < k; j0 += kArgGenerators) {
+                const int cnt = k - j0 < kArgGenerators ? k - j0 : kArgGenerators;
+                IdxByValue ia;
+                for (int j = 0; j < kArgGenerators; ++j) ia.v[j] = j < cnt ? idx_host[j0 + j] : 0;
+                hipLaunchKernelGGL((k_gather_arg<TR>), dim3(cnt), dim3(256), 0, s, (const u32x4_t*)X, ia, j0, b, nch, (u32x4_t*)C, idx,
+                                   inv, cn2, hash, eta);
+            }
+        }
     }
     {
         ScopedSpan span(kScore, s);
@@ -781,41 +784,9 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }
 
-static pamm_status check_compress_args(const void* X, int64_t b, int64_t n, int64_t k, pamm_dtype dt, void* C, int32_t* f,
-                                       float* alpha, void* ws, size_t ws_bytes, CompressPlan* pl) {
-    pamm_status st = plan_compress(b, n, k, dt, pl);
-    if (st != PAMM_OK) return st;
-    if (!X || !C || !f || !alpha) return PAMM_ERR_INVALID_ARG;
-    if (!aligned16(X) || !aligned16(C) || !aligned16(f) || !aligned16(alpha)) return PAMM_ERR_INVALID_ARG;
-    if (!ws || ws_bytes < pl->total) return PAMM_ERR_WORKSPACE;
-    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
-    return PAMM_OK;
-}
-
-// ---- pinned ring that carries more than kArgGenerators sampled indices to the gather kernel without a copy or a sync ----
-constexpr int kRingSlots = 32;
-constexpr int kMaxDevices = 16;
-struct IdxRing {
-    int32_t* host = nullptr;
-    int32_t* dev = nullptr;
-    hipEvent_t ev[kRingSlots];
-    bool used[kRingSlots] = {};
-    int next = 0;
-    bool ready = false;
-};
-static IdxRing g_ring[kMaxDevices];
-static std::mutex g_ring_mu;
-
 }  // namespace pamm
 
 using namespace pamm;
-
-// eps -> keep = 1 - eps^2 (negative: the condition cannot drop anything and is switched off)
-static pamm_status keep_of(float eps, double* keep) {
-    if (!(eps >= 0.f)) return PAMM_ERR_INVALID_ARG;          // negative or NaN
-    *keep = eps < 1.f ? 1.0 - double(eps) * double(eps) : -1.0;
-    return PAMM_OK;
-}
 
 static pamm_status compress_idx_impl(const void* X, int64_t b, int64_t n, int64_t k, const int32_t* idx_dev, double keep,
                                      pamm_dtype dt, void* C, int32_t* f, float* alpha, int32_t* eta, void* ws, size_t ws_bytes,
@@ -837,47 +808,13 @@ static pamm_status compress_seed_impl(const void* X, int64_t b, int64_t n, int64
     if (st != PAMM_OK) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
-    if (k <= kArgGenerators) {          // the sampled row numbers travel in the gather kernel's argument block
-        IdxByValue ia;
-        st = pamm_sample_indices(b, k, seed, ia.v);
-        if (st != PAMM_OK) return st;
-        for (int64_t j = k; j < kArgGenerators; ++j) ia.v[j] = 0;
-        if (dt == PAMM_BF16)
-            return run_compress<Bf16>(pl, X, int(b), int(n), int(k), nullptr, &ia, keep, C, f, alpha, eta, (char*)ws, s);
-        return run_compress<F32>(pl, X, int(b), int(n), int(k), nullptr, &ia, keep, C, f, alpha, eta, (char*)ws, s);
-    }
-
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return PAMM_ERR_DEVICE;
-
-    std::lock_guard<std::mutex> lock(g_ring_mu);
-    IdxRing& ring = g_ring[device];
-    if (!ring.ready) {
-        void* h = nullptr;
-        if (hipHostMalloc(&h, size_t(kRingSlots) * kMaxGenerators * sizeof(int32_t), hipHostMallocDefault) != hipSuccess)
-            return PAMM_ERR_DEVICE;
-        void* d = nullptr;
-        if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) { (void)hipHostFree(h); return PAMM_ERR_DEVICE; }
-        for (int i = 0; i < kRingSlots; ++i)
-            if (hipEventCreateWithFlags(&ring.ev[i], hipEventDisableTiming) != hipSuccess) return PAMM_ERR_DEVICE;
-        ring.host = static_cast<int32_t*>(h);
-        ring.dev = static_cast<int32_t*>(d);
-        ring.ready = true;
-    }
-    const int slot = ring.next;
-    ring.next = (ring.next + 1) % kRingSlots;
-    // a slot is reused only after the gather kernel that read it has finished (32 calls ago: normally long done)
-    if (ring.used[slot] && hipEventSynchronize(ring.ev[slot]) != hipSuccess) return PAMM_ERR_DEVICE;
-    int32_t* hidx = ring.host + size_t(slot) * kMaxGenerators;
-    st = pamm_sample_indices(b, k, seed, hidx);
+    // the sampled row numbers travel in the gather kernels' argument blocks
+    int32_t idx_host[kMaxGenerators];
+    st = pamm_sample_indices(b, k, seed, idx_host);
     if (st != PAMM_OK) return st;
-    const int32_t* didx = ring.dev + size_t(slot) * kMaxGenerators;
-
-    if (dt == PAMM_BF16) st = run_compress<Bf16>(pl, X, int(b), int(n), int(k), didx, nullptr, keep, C, f, alpha, eta, (char*)ws, s);
-    else st = run_compress<F32>(pl, X, int(b), int(n), int(k), didx, nullptr, keep, C, f, alpha, eta, (char*)ws, s);
-    if (hipEventRecord(ring.ev[slot], s) != hipSuccess) return PAMM_ERR_DEVICE;
-    ring.used[slot] = true;
-    return st;
+    if (dt == PAMM_BF16)
+        return run_compress<Bf16>(pl, X, int(b), int(n), int(k), nullptr, idx_host, keep, C, f, alpha, eta, (char*)ws, s);
+    return run_compress<F32>(pl, X, int(b), int(n), int(k), nullptr, idx_host, keep, C, f, alpha, eta, (char*)ws, s);
 }
 
 extern "C" pamm_status pamm_compress_idx(const void* X, int64_t b, int64_t n, int64_t k, const int32_t* idx_dev, pamm_dtype dt,
@@ -894,13 +831,13 @@ extern "C" pamm_status pamm_compress_idx_eps(const void* X, int64_t b, int64_t n
                                              pamm_dtype dt, void* C, int32_t* f, float* alpha, int32_t* eta, void* ws,
                                              size_t ws_bytes, void* stream) {
     double keep;
-    if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
+    if (!eta || !aligned4(eta) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
     return compress_idx_impl(X, b, n, k, idx_dev, keep, dt, C, f, alpha, eta, ws, ws_bytes, stream);
 }
 
 extern "C" pamm_status pamm_compress_eps(const void* X, int64_t b, int64_t n, int64_t k, uint64_t seed, float eps, pamm_dtype dt,
                                          void* C, int32_t* f, float* alpha, int32_t* eta, void* ws, size_t ws_bytes, void* stream) {
     double keep;
-    if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
+    if (!eta || !aligned4(eta) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
     return compress_seed_impl(X, b, n, k, seed, keep, dt, C, f, alpha, eta, ws, ws_bytes, stream);
 }

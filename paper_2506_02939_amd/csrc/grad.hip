@@ -55,8 +55,46 @@ __device__ __forceinline__ void load_keys(const int32_t* __restrict__ f, const f
     }
 }
 
+// One row's key (as load_keys) and weight; rows past the end count as "no row".
+__device__ __forceinline__ int load_key(const int32_t* __restrict__ f, const float* __restrict__ alpha, int i, int b, int k, float& w) {
+    const bool in = i < b;
+    const int ii = in ? i : b - 1;
+    int v = f[ii];
+    w = alpha[ii];
+    v = v < 0 ? 0 : (v >= k ? k - 1 : v);
+    return (in && w != 0.f) ? v : k;
+}
+
+// The lanes of the wave whose key equals this lane's (this lane included): the key's bits are peeled off one ballot
+// at a time, so the cost does not depend on how many different keys the wave holds.  nbits covers the values 0..k.
+__device__ __forceinline__ unsigned long long lanes_with_my_key(int key, int nbits) {
+    unsigned long long same = ~0ull;
+    for (int bit = 0; bit < nbits; ++bit) {
+        const bool set = (key >> bit) & 1;
+        const unsigned long long bal = __ballot(set);
+        same &= set ? bal : ~bal;
+    }
+    return same;
+}
+
+// Position of a row inside its generator's part of the sorted list, for the 64 rows (one per lane, in increasing
+// row order) that a wave places at a time: `ctr` points at the wave's own LDS counter for this lane's generator
+// (rows of the generator the wave has placed so far, on top of the rows of earlier waves and slices).  Equal keys
+// take consecutive positions in lane order, so together with the order of the calls the rows of one generator
+// stay in increasing row order: the sort is stable by construction, no atomic decides an order.
+__device__ __forceinline__ int stable_slot(int* ctr, bool live, int key, int nbits) {
+    const unsigned long long same = lanes_with_my_key(key, nbits);
+    const int lane = threadIdx.x & 63;
+    const int rank = __popcll(same & ((1ull << lane) - 1ull));
+    int old = 0;
+    if (live) old = *ctr;                                   // every lane of the group reads before its leader writes
+    wave_lds_sync();
+    if (live && rank == 0) *ctr = old + __popcll(same);
+    wave_lds_sync();
+    return old + rank;
+}
+
 // What the grouping kernels leave for k_contract: hdr[0] = L, entries in the list; hdr[1] = P, positions per chunk.
-constexpr int kHdrInts = 4;
 
 // Chunk size for a list of L entries: one chunk per CU and workgroup column (256 CUs), a multiple of 16, at most 4096;
 // p_fixed > 0 overrides (tuning).  The host sizes the partial-row buffer for the largest chunk count this can give.
@@ -222,10 +260,12 @@ __global__ __launch_bounds__(1024) void k_group_regs(const int32_t* __restrict__
 // Grouping in O(b) for k <= 2048: a counting sort over slices of 4*NT rows (NT threads per workgroup).
 //   k_hist     one workgroup per slice: histogram of the slice's keys (LDS atomics), written to table[slice][j]
 //   k_scatter  one workgroup per slice: start of every generator's list (sum over all slices, scanned over j), plus
-//              the rows of earlier slices, plus the rows of earlier waves of this slice; then every row takes the
-//              next free position of its (wave, generator) counter and writes its 16-byte list entry.
-// Inside a wave the order of equal keys is the order in which the LDS unit serves the lanes of one atomic
-// instruction; it does not depend on timing, so the list, and every sum formed from it, is the same on every call.
+//              the rows of earlier slices, plus the rows of earlier waves of this slice; then every row takes its
+//              position behind the rows of its generator that precede it and writes its 16-byte list entry.
+// Wave w of a slice owns its rows [256 w, 256 w + 256) and places them 64 at a time in increasing order; equal keys
+// inside such a group of 64 take consecutive positions in lane order (stable_slot), so the rows of one generator stay
+// in increasing row order whatever the hardware does: the list, and every sum formed from it, is the same on every
+// call, and the same as the per-generator grouping kernels produce.
 constexpr int kScatterMaxK = 2048;     // (NT/64 + 2) * k ints of LDS
 
 template <int NT>
@@ -261,11 +301,10 @@ __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, c
     // every global load of the kernel is issued up front (keys, weights, this thread's share of the table), so the
     // kernel pays one memory latency, not one per phase
     int key[4];
-    const int i0 = slice * (4 * NT) + 4 * tid;        // wave w owns rows [256 w, 256 w + 256) of the slice
-    load_keys(f, alpha, i0, b, k, key);
     float al[4];
+    const int i0 = slice * (4 * NT) + 256 * wave + lane;      // wave w owns rows [256 w, 256 w + 256) of the slice; slot c: + 64 c
 #pragma unroll
-    for (int c = 0; c < 4; ++c) al[c] = alpha[min(i0 + c, b - 1)];
+    for (int c = 0; c < 4; ++c) key[c] = load_key(f, alpha, i0 + 64 * c, b, k, al[c]);
     // rows of every generator in earlier slices / in all slices: column sums of the table, taken in parallel by all
     // threads: `strips` threads per generator when there are fewer generators than threads, each summing every
     // strips-th slice; otherwise every thread sums whole columns for the generators tid, tid + NT, ...
@@ -351,12 +390,15 @@ __global__ __launch_bounds__(NT) void k_scatter(const int32_t* __restrict__ f, c
         if (tid == 0) { hdr[0] = L; hdr[1] = P; }
     }
 
+    const int nbits = 32 - __clz(k);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        if (key[c] < k) {
-            const int pos = tot[key[c]] + atomicAdd(&wh[wave * k + key[c]], 1);
-            list[pos] = list_entry(i0 + c, al[c], key[c]);
-            if (pos == L - 1) pad_list(list, L, i0 + c, key[c]);
+        const bool live = key[c] < k;
+        const int kc = live ? key[c] : 0;
+        const int pos = tot[kc] + stable_slot(&wh[wave * k + kc], live, key[c], nbits);
+        if (live) {
+            list[pos] = list_entry(i0 + 64 * c, al[c], key[c]);
+            if (pos == L - 1) pad_list(list, L, i0 + 64 * c, key[c]);
         }
     }
 }
@@ -382,12 +424,9 @@ __global__ __launch_bounds__(1024) void k_sort_one(const int32_t* __restrict__ f
     int key[Q][4];
     float al[Q][4];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int i0 = r0 + q * 256 + 4 * lane;
-        load_keys(f, alpha, i0, b, k, key[q]);
+    for (int q = 0; q < Q; ++q)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) al[q][c] = alpha[max(0, min(i0 + c, b - 1))];
-    }
+        for (int c = 0; c < 4; ++c) key[q][c] = load_key(f, alpha, r0 + (4 * q + c) * 64 + lane, b, k, al[q][c]);      // slot 4 q + c
     for (int q = tid; q < (NWV + 2) * k; q += NT) wh[q] = 0;      // wh, tot and cnt are contiguous
     __syncthreads();
 #pragma unroll
@@ -445,15 +484,18 @@ __global__ __launch_bounds__(1024) void k_sort_one(const int32_t* __restrict__ f
     }
     if (tid == 0) { hdr[0] = L; hdr[1] = P; }
 
+    const int nbits = 32 - __clz(k);
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-        const int i0 = r0 + q * 256 + 4 * lane;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (key[q][c] < k) {
-                const int pos = tot[key[q][c]] + atomicAdd(&wh[wave * k + key[q][c]], 1);
-                list[pos] = list_entry(i0 + c, al[q][c], key[q][c]);
-                if (pos == L - 1) pad_list(list, L, i0 + c, key[q][c]);
+            const int row = r0 + (4 * q + c) * 64 + lane;
+            const bool live = key[q][c] < k;
+            const int kc = live ? key[q][c] : 0;
+            const int pos = tot[kc] + stable_slot(&wh[wave * k + kc], live, key[q][c], nbits);
+            if (live) {
+                list[pos] = list_entry(row, al[q][c], key[q][c]);
+                if (pos == L - 1) pad_list(list, L, row, key[q][c]);
             }
         }
     }
@@ -541,10 +583,7 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     // onto its last group, which is in cache by then), so the wait before a group's sums only has to cover that
     // group and the two younger ones stay in flight.  The sorted list is padded to a multiple of 16 entries
     // (weight 0, last key, a valid row), so a group never needs a guard.
-#ifndef PAMM_CONTRACT_U
-#define PAMM_CONTRACT_U 0
-#endif
-    constexpr int U = PAMM_CONTRACT_U ? PAMM_CONTRACT_U : ((RowLoad<TR>::kGroup / W) < 2 ? 2 : (RowLoad<TR>::kGroup / W));
+    constexpr int U = (RowLoad<TR>::kGroup / W) < 2 ? 2 : (RowLoad<TR>::kGroup / W);
     static_assert(16 % (2 * U) == 0, "a chunk must be a whole number of group pairs");
     const int last = (s1 + 2 * U - 1) / (2 * U) * (2 * U) - U;      // start of the chunk's last group
     // list entries (row number, weight, generator: wave-uniform, so they travel through scalar registers)
@@ -877,8 +916,6 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 
 // ------------------------------------------------------------------------------------------------ host side
 
-static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
 struct GradBuffers {
     int32_t *sbase, *snum, *table, *hdr;
     float* partial;
@@ -983,13 +1020,8 @@ using namespace pamm;
 extern "C" pamm_status pamm_contract(const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t k, int64_t m,
                                      pamm_dtype dt, float* Btilde, void* ws, size_t ws_bytes, void* stream) {
     GradPlan pl;
-    pamm_status st = plan_grad(b, per_chunk(dtype_ok(dt) ? dt : PAMM_F32), k, m, dt, &pl);   // n does not enter what is used here
+    pamm_status st = check_contract_args(f, alpha, dY, b, k, m, dt, Btilde, ws, ws_bytes, &pl);
     if (st != PAMM_OK) return st;
-    if (k > b) return PAMM_ERR_INVALID_ARG;
-    if (!f || !alpha || !dY || !Btilde) return PAMM_ERR_INVALID_ARG;
-    if (!aligned16(f) || !aligned16(alpha) || !aligned16(dY) || !aligned16(Btilde)) return PAMM_ERR_INVALID_ARG;
-    if (!ws || ws_bytes < pl.total) return PAMM_ERR_WORKSPACE;
-    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     GradBuffers g = carve(pl, (char*)ws);
     if (dt == PAMM_BF16) launch_group_contract<Bf16>(pl, g, f, alpha, dY, int(b), int(k), int(m), s);
@@ -1006,16 +1038,9 @@ static pamm_status grad_impl(const void* C, const int32_t* f, const float* alpha
                              int64_t n, int64_t k, int64_t m, pamm_dtype dt, pamm_dtype out_dt, pamm_layout layout, void* dW,
                              void* ws, size_t ws_bytes, void* stream) {
     GradPlan pl;
-    pamm_status st = plan_grad(b, n, k, m, dt, &pl);
+    pamm_status st = check_grad_args(C, f, alpha, dY, b, n, k, m, dt, out_dt, layout, dW, ws, ws_bytes, &pl);
     if (st != PAMM_OK) return st;
-    if (!dtype_ok(out_dt) || (layout != PAMM_DW_N_BY_M && layout != PAMM_DW_M_BY_N)) return PAMM_ERR_UNSUPPORTED;
-    if (out_dt == PAMM_BF16 && (((layout == PAMM_DW_M_BY_N) ? n : m) & 1)) return PAMM_ERR_UNSUPPORTED;   // pairs of columns
     const bool out16 = out_dt == PAMM_BF16, m_by_n = layout == PAMM_DW_M_BY_N;
-    if (k > b) return PAMM_ERR_INVALID_ARG;
-    if (!C || !f || !alpha || !dY || !dW) return PAMM_ERR_INVALID_ARG;
-    if (!aligned16(C) || !aligned16(f) || !aligned16(alpha) || !aligned16(dY) || !aligned16(dW)) return PAMM_ERR_INVALID_ARG;
-    if (!ws || ws_bytes < pl.total) return PAMM_ERR_WORKSPACE;
-    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     GradBuffers g = carve(pl, (char*)ws);
     if (dt == PAMM_BF16) {
@@ -1036,13 +1061,13 @@ extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* a
 extern "C" pamm_status pamm_grad_eps(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY,
                                      int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, float* dW, void* ws,
                                      size_t ws_bytes, void* stream) {
-    if (!eta || (reinterpret_cast<uintptr_t>(eta) & 3u)) return PAMM_ERR_INVALID_ARG;
+    if (!eta || !aligned4(eta)) return PAMM_ERR_INVALID_ARG;
     return grad_impl(C, f, alpha, eta, dY, b, n, k, m, dt, PAMM_F32, PAMM_DW_N_BY_M, dW, ws, ws_bytes, stream);
 }
 
 extern "C" pamm_status pamm_grad_out(const void* C, const int32_t* f, const float* alpha, const int32_t* eta, const void* dY,
                                      int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt, pamm_dtype out_dt,
                                      pamm_layout layout, void* dW, void* ws, size_t ws_bytes, void* stream) {
-    if (eta && (reinterpret_cast<uintptr_t>(eta) & 3u)) return PAMM_ERR_INVALID_ARG;
+    if (eta && !aligned4(eta)) return PAMM_ERR_INVALID_ARG;
     return grad_impl(C, f, alpha, eta, dY, b, n, k, m, dt, out_dt, layout, dW, ws, ws_bytes, stream);
 }

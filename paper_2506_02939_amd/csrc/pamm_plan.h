@@ -3,7 +3,6 @@
 
 #include <stddef.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "../../include/pamm.h"
 
@@ -19,16 +18,15 @@ inline int per_chunk(pamm_dtype dt) { return dt == PAMM_BF16 ? 8 : 4; }
 
 inline bool dtype_ok(pamm_dtype dt) { return dt == PAMM_F32 || dt == PAMM_BF16; }
 
-// Tuning overrides for experiments (read on every call; unset or invalid = use the built-in heuristic):
-//   PAMM_SCORE_TG    32-generator fragments per wave in k_score (1, 2, 4 or 8; at most what k allows)
-//   PAMM_SCORE_NW    waves per workgroup in k_score (2, 4 or 8)
-//   PAMM_PIECE_ROWS  list positions per chunk in k_contract (a multiple of 16, 16..4096)
-//   PAMM_CONTRACT_W  512-column groups per wave in k_contract (1..3)
-//   PAMM_SORT_ONE    largest b sorted by the single-workgroup kernel (1..16384)
-inline int env_int(const char* name) {
-    const char* v = getenv(name);
-    return v ? atoi(v) : 0;
-}
+// Overrides of the built-in launch heuristics, set only through the test hook pamm_debug_set_plan (0 = heuristic).
+// Product calls never read the environment; tests use the hook to reach the kernel variants and grid decompositions
+// that the heuristics do not pick at the shapes they run.
+//   score_tg       32-generator fragments per wave in k_score (1, 2, 4 or 8; at most what k allows)
+//   score_nw       waves per workgroup in k_score (2, 4 or 8)
+//   piece_rows     list positions per chunk in k_contract (a multiple of 16, 16..4096)
+//   contract_w     512-column groups per wave in k_contract (1..3)
+//   sort_one_rows  largest b sorted by the single-workgroup kernel (1..16384)
+extern pamm_debug_plan g_plan_override;
 
 // ------------------------------------------------------------------------------------ compress
 
@@ -64,10 +62,10 @@ inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt,
         nw = 8;
         while (nw > 2 && tiles(nw) * blocks(tg) < 224) nw /= 2;
     }
-    const int tg_env = env_int("PAMM_SCORE_TG");
-    if ((tg_env == 1 || tg_env == 2 || tg_env == 4 || tg_env == 8) && tg_env <= tg_max) tg = tg_env;
-    const int nw_env = env_int("PAMM_SCORE_NW");
-    if (nw_env == 2 || nw_env == 4 || nw_env == 8) nw = nw_env;
+    const int tg_forced = g_plan_override.score_tg;
+    if ((tg_forced == 1 || tg_forced == 2 || tg_forced == 4 || tg_forced == 8) && tg_forced <= tg_max) tg = tg_forced;
+    const int nw_forced = g_plan_override.score_nw;
+    if (nw_forced == 2 || nw_forced == 4 || nw_forced == 8) nw = nw_forced;
     p->tg = tg;
     p->ncb = int(blocks(tg));
     p->tt = 1;
@@ -87,7 +85,7 @@ inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt,
 // ---------------------------------------------------------------------------------------- grad
 
 struct GradPlan {
-    int p_fixed;          // chunk size forced by PAMM_PIECE_ROWS (0: chosen on the device from the length of the list)
+    int p_fixed;          // chunk size forced by the test hook (0: chosen on the device from the length of the list)
     int64_t chunks;       // upper bound on the number of chunks the sorted list is cut into
     int64_t nslots;       // upper bound on piece numbers: chunks + k
     int col_groups;       // ceil(m / 512)
@@ -109,19 +107,19 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     p->col_groups = int((m + 511) / 512);
     int W = (p->col_groups + 3) / 4;
     W = W < 1 ? 1 : (W > 3 ? 3 : W);
-    const int w_env = env_int("PAMM_CONTRACT_W");
-    if (w_env >= 1 && w_env <= 3) W = w_env;
+    const int w_forced = g_plan_override.contract_w;
+    if (w_forced >= 1 && w_forced <= 3) W = w_forced;
     p->wave_groups = W;
-    const int so_env = env_int("PAMM_SORT_ONE");
-    p->sort_one_rows = (so_env >= 1 && so_env <= 16384) ? so_env : 8192;
+    const int so_forced = g_plan_override.sort_one_rows;
+    p->sort_one_rows = (so_forced >= 1 && so_forced <= 16384) ? so_forced : 8192;
     p->wg_cols = (p->col_groups + 4 * W - 1) / (4 * W);
     // One workgroup per (chunk, 4*W column groups).  All workgroups carry the same load, and measured on the
     // MI355X the contraction runs best as one even round: exactly one workgroup per CU (256 CUs), i.e. few, long
     // chunks (4 waves per CU, each with >= 12 KiB of dY in flight).  The list only holds the rows with a non-zero
     // weight, L <= b of them, so the chunk size P = clamp(roundup16(L * wg_cols / 256), 16, 4096) is set on the
     // device; whatever L is, that gives at most max(ceil(256 / wg_cols), ceil(b / 4096)) + 1 chunks.
-    const int p_env = env_int("PAMM_PIECE_ROWS");
-    p->p_fixed = (p_env >= 16 && p_env <= 4096 && p_env % 16 == 0) ? p_env : 0;
+    const int p_forced = g_plan_override.piece_rows;
+    p->p_fixed = (p_forced >= 16 && p_forced <= 4096 && p_forced % 16 == 0) ? p_forced : 0;
     if (p->p_fixed) {
         p->chunks = (b + p->p_fixed - 1) / p->p_fixed;
     } else {
@@ -145,6 +143,58 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
     p->off_ct = o;      o = align_up(o + size_t(n) * size_t(p->kpad) * elem_bytes(dt), 256);
     p->off_bt = o;      o = align_up(o + size_t(m) * size_t(p->kpad) * elem_bytes(dt), 256);
     p->total = o;
+    return PAMM_OK;
+}
+
+// ------------------------------------------------------------------------- argument checks of the entry points
+// All of them run on the host before anything is enqueued; kept here, free of device code, so that a plain CPU build
+// can run them under the address and undefined-behaviour sanitizers.
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+inline pamm_status check_compress_args(const void* X, int64_t b, int64_t n, int64_t k, pamm_dtype dt, const void* C, const void* f,
+                                       const void* alpha, const void* ws, size_t ws_bytes, CompressPlan* pl) {
+    pamm_status st = plan_compress(b, n, k, dt, pl);
+    if (st != PAMM_OK) return st;
+    if (!X || !C || !f || !alpha) return PAMM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(C) || !aligned16(f) || !aligned16(alpha)) return PAMM_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < pl->total) return PAMM_ERR_WORKSPACE;
+    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
+    return PAMM_OK;
+}
+
+// eps -> keep = 1 - eps^2 (negative: the condition cannot drop anything and is switched off)
+inline pamm_status keep_of(float eps, double* keep) {
+    if (!(eps >= 0.f)) return PAMM_ERR_INVALID_ARG;          // negative or NaN
+    *keep = eps < 1.f ? 1.0 - double(eps) * double(eps) : -1.0;
+    return PAMM_OK;
+}
+
+inline pamm_status check_contract_args(const void* f, const void* alpha, const void* dY, int64_t b, int64_t k, int64_t m,
+                                       pamm_dtype dt, const void* Btilde, const void* ws, size_t ws_bytes, GradPlan* pl) {
+    pamm_status st = plan_grad(b, per_chunk(dtype_ok(dt) ? dt : PAMM_F32), k, m, dt, pl);   // n does not enter what is used
+    if (st != PAMM_OK) return st;
+    if (k > b) return PAMM_ERR_INVALID_ARG;
+    if (!f || !alpha || !dY || !Btilde) return PAMM_ERR_INVALID_ARG;
+    if (!aligned16(f) || !aligned16(alpha) || !aligned16(dY) || !aligned16(Btilde)) return PAMM_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < pl->total) return PAMM_ERR_WORKSPACE;
+    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
+    return PAMM_OK;
+}
+
+inline pamm_status check_grad_args(const void* C, const void* f, const void* alpha, const void* dY, int64_t b, int64_t n, int64_t k,
+                                   int64_t m, pamm_dtype dt, pamm_dtype out_dt, pamm_layout layout, const void* dW, const void* ws,
+                                   size_t ws_bytes, GradPlan* pl) {
+    pamm_status st = plan_grad(b, n, k, m, dt, pl);
+    if (st != PAMM_OK) return st;
+    if (!dtype_ok(out_dt) || (layout != PAMM_DW_N_BY_M && layout != PAMM_DW_M_BY_N)) return PAMM_ERR_UNSUPPORTED;
+    if (out_dt == PAMM_BF16 && (((layout == PAMM_DW_M_BY_N) ? n : m) & 1)) return PAMM_ERR_UNSUPPORTED;   // pairs of columns
+    if (k > b) return PAMM_ERR_INVALID_ARG;
+    if (!C || !f || !alpha || !dY || !dW) return PAMM_ERR_INVALID_ARG;
+    if (!aligned16(C) || !aligned16(f) || !aligned16(alpha) || !aligned16(dY) || !aligned16(dW)) return PAMM_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < pl->total) return PAMM_ERR_WORKSPACE;
+    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
     return PAMM_OK;
 }
 

@@ -25,6 +25,7 @@ EXPORTS = [
     "pamm_compress", "pamm_compress_idx", "pamm_compress_eps", "pamm_compress_idx_eps", "pamm_grad", "pamm_grad_eps",
     "pamm_grad_out", "pamm_contract",
     "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
+    "pamm_debug_set_plan", "pamm_debug_bounded",
 ]
 NUM_KERNELS = 8
 
@@ -72,6 +73,10 @@ def _load() -> ctypes.CDLL:
     lib.pamm_profile_end.restype = ci
     lib.pamm_kernel_name.argtypes = [ci]
     lib.pamm_kernel_name.restype = ctypes.c_char_p
+    lib.pamm_debug_set_plan.argtypes = [vp]
+    lib.pamm_debug_set_plan.restype = ci
+    lib.pamm_debug_bounded.argtypes = [u64, u64, i64, vp]
+    lib.pamm_debug_bounded.restype = ci
     return lib
 
 
@@ -222,6 +227,27 @@ def contract(f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, k: int, *, 
                            ws.numel(), _stream())
     _check(st, "pamm_contract")
     return out
+
+
+class _DebugPlan(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int) for name in ("score_tg", "score_nw", "piece_rows", "contract_w", "sort_one_rows")]
+
+
+def debug_set_plan(**overrides: int) -> None:
+    """pamm_debug_set_plan (test hook): force launch-plan fields; no arguments clears every override."""
+    if not overrides:
+        _check(lib.pamm_debug_set_plan(None), "pamm_debug_set_plan")
+        return
+    plan = _DebugPlan(**{k: int(v) for k, v in overrides.items()})
+    _check(lib.pamm_debug_set_plan(ctypes.addressof(plan)), "pamm_debug_set_plan")
+
+
+def debug_bounded(seed: int, range_: int, count: int) -> list:
+    """pamm_debug_bounded (test hook): `count` draws of the sampler's bounded step on [0, range_)."""
+    out = (ctypes.c_uint64 * max(count, 1))()
+    _check(lib.pamm_debug_bounded(ctypes.c_uint64(seed & (2**64 - 1)), ctypes.c_uint64(range_), count, ctypes.addressof(out)),
+           "pamm_debug_bounded")
+    return [int(out[i]) for i in range(count)]
 
 
 def profile_begin() -> None:

@@ -45,6 +45,36 @@ def test_sampler_matches_oracle_stream(pamm, oracle, b, k, seed):
     assert np.array_equal(got, oracle.sample(b, k, seed))
 
 
+def test_bounded_draw_hook_takes_the_rejection_branch_like_the_specification(pamm, oracle):
+    """The library's bounded step on ranges near 2^63 (rejection probability 1/4 .. 1/2): against the published
+    splitmix64 outputs reduced with exact integers, and draw for draw against the oracle's independent implementation."""
+    golden = os.path.join(ROOT, "tests", "golden", "splitmix64_seed1234567.txt")
+    pub = [int(line) for line in open(golden) if line.strip() and not line.startswith("#")]
+    for u in (3 << 62, (1 << 63) + 12345, (1 << 62) + 1, 5):
+        cut = (1 << 64) % u
+        want = [x % u for x in pub if x >= cut]
+        assert pamm.debug_bounded(1234567, u, len(want)) == want
+        for seed in (0, 99, 2**64 - 1):
+            assert pamm.debug_bounded(seed, u, 500) == [int(v) for v in oracle.bounded(seed, u, 500)]
+    assert pamm.lib.pamm_debug_bounded(0, 0, 1, ctypes.addressof((ctypes.c_uint64 * 1)())) == pamm.PAMM_ERR_INVALID_ARG
+    assert pamm.lib.pamm_debug_bounded(0, 5, 1, None) == pamm.PAMM_ERR_INVALID_ARG
+
+
+def test_plan_overrides_enter_the_workspace_query_and_can_be_cleared(pamm):
+    base = pamm.grad_workspace(65536, 2048, 128, 6144, pamm.PAMM_BF16)
+    try:
+        pamm.debug_set_plan(piece_rows=16)
+        assert pamm.grad_workspace(65536, 2048, 128, 6144, pamm.PAMM_BF16) > base       # 4096 chunks of partial rows
+        pamm.debug_set_plan(piece_rows=17)                                              # out of range: heuristic stays
+        assert pamm.grad_workspace(65536, 2048, 128, 6144, pamm.PAMM_BF16) == base
+        c0 = pamm.compress_workspace(16384, 4096, 1024, pamm.PAMM_BF16)
+        pamm.debug_set_plan(score_tg=1)
+        assert pamm.compress_workspace(16384, 4096, 1024, pamm.PAMM_BF16) > c0           # 32 column blocks of records
+    finally:
+        pamm.debug_set_plan()
+    assert pamm.grad_workspace(65536, 2048, 128, 6144, pamm.PAMM_BF16) == base
+
+
 def test_sampler_rejects_bad_arguments(pamm):
     buf = (ctypes.c_int32 * 4)()
     assert pamm.lib.pamm_sample_indices(4, 5, 0, ctypes.addressof(buf)) == pamm.PAMM_ERR_INVALID_ARG

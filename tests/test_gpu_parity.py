@@ -16,6 +16,16 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 2e-2}          # spec bars
 TOL_ALPHA = 2e-5                           # fp32 accumulation
 TOL_DW = {"f32": 2e-5, "bf16": 2.0 ** -8}  # + one bf16 rounding of Btilde
+# Element-wise bars, each relative to the magnitude that bounds the element's rounding error (so that a few wrong
+# elements, or one bad tile, cannot hide in a Frobenius norm):
+#   alpha_i   against ||X_i|| / ||C_f(i)||  (Cauchy-Schwarz bound of |<X_i,C_j>| / ||C_j||^2): fp32 accumulation of n terms
+#   Btilde    against sum_i |alpha_i| |dY_i|  over the generator's rows: fp32 summation in list order
+#   dW        against |C|^T (sum_i w_i |dY_i|), w_i = |alpha_i| when (f, alpha) are given, ||X_i||/||C_f(i)|| when alpha
+#             is the GPU's own; bf16 inputs add the one bf16 rounding of Btilde (2^-9 of |Btilde| <= the same bound)
+ELEM_ALPHA = 1e-5                                      # measured worst 2.9e-6 (rows of 16384 fp32 elements)
+ELEM_BT = 5e-6                                         # measured worst 5.7e-7
+ELEM_DW = {"f32": 5e-6, "bf16": 2.0 ** -8 + 5e-6}      # measured worst 6.9e-7 / 2.4e-3; 2^-8 is bf16's unit roundoff
+WORST = {}                                 # largest ratios seen, printed with every case
 
 
 @pytest.fixture(scope="module")
@@ -31,6 +41,15 @@ def rel_fro(a, ref):
     ref = np.asarray(ref, dtype=np.float64)
     den = np.linalg.norm(ref)
     return float(np.linalg.norm(a - ref) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def elem_ratio(got, ref, scale):
+    """max over elements of |got - ref| / scale (elements whose scale is 0 must agree exactly)."""
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - ref)
+    zero = scale <= 0
+    assert not np.any(err[zero] > 0), "an element with no contribution at all is not exactly zero"
+    return float(np.max(err[~zero] / scale[~zero])) if np.any(~zero) else 0.0
 
 
 def raw_bits(t: torch.Tensor) -> np.ndarray:
@@ -80,17 +99,26 @@ def run_case(pamm, oracle, X, dY, k, dtype_name, *, seed=0, idx=None, label=""):
     assert np.isfinite(a_gpu).all()
     e_alpha = rel_fro(a_gpu[agree], ora.alpha[agree])
     assert e_alpha <= TOL[dtype_name] and e_alpha <= TOL_ALPHA, f"alpha error {e_alpha}"
+    cnorm = np.sqrt((ora.C ** 2).sum(axis=1))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        w_bound = np.where(cnorm[f_gpu] > 0, ora.rownorm / cnorm[f_gpu], 0.0)      # >= |alpha_i| for the GPU's assignment
+    r_alpha = elem_ratio(a_gpu[agree], ora.alpha[agree], w_bound[agree])
+    assert r_alpha <= ELEM_ALPHA, f"alpha: an element is off by {r_alpha} of ||X_i||/||C_f(i)||"
 
     # ApproxMM on the GPU's own (C, f, alpha)
     Bt_or, O_or = oracle.grad(ora.C, ora.f, ora.alpha, dY)
     dW = pamm.grad(got.C, got.f, got.alpha, dYg)
     torch.cuda.synchronize()
     if ndiff == 0:
-        e_dw = rel_fro(dW.cpu().numpy(), O_or)
+        O_cmp = O_or
     else:   # rows at a near-tie went to another (equally good) generator: compare with the oracle on the GPU's choice
-        _, O_alt = oracle.grad(ora.C, f_gpu, a_gpu, dY)
-        e_dw = rel_fro(dW.cpu().numpy(), O_alt)
+        _, O_cmp = oracle.grad(ora.C, f_gpu, a_gpu, dY)
+    e_dw = rel_fro(dW.cpu().numpy(), O_cmp)
     assert e_dw <= TOL[dtype_name] and e_dw <= TOL_DW[dtype_name], f"dW error {e_dw}"
+    absC, absdY = np.abs(ora.C), dY.abs()
+    _, O_bound = oracle.grad(absC, f_gpu, w_bound, absdY)
+    r_dw = elem_ratio(dW.cpu().numpy(), O_cmp, O_bound)
+    assert r_dw <= ELEM_DW[dtype_name], f"dW: an element is off by {r_dw} of its bound"
 
     # ApproxMM fed with the oracle's (f, alpha): isolates the contraction and the C^T Btilde product
     f_in = torch.from_numpy(ora.f).cuda()
@@ -103,7 +131,15 @@ def run_case(pamm, oracle, X, dY, k, dtype_name, *, seed=0, idx=None, label=""):
     e_dw2 = rel_fro(dW2.cpu().numpy(), O_or)
     assert e_bt <= TOL_ALPHA, f"Btilde error {e_bt}"
     assert e_dw2 <= TOL[dtype_name] and e_dw2 <= TOL_DW[dtype_name], f"dW (oracle f, alpha) error {e_dw2}"
+    Bt_abs, O_abs = oracle.grad(absC, ora.f, np.abs(ora.alpha), absdY)
+    r_bt = elem_ratio(Bt.cpu().numpy(), Bt_or, Bt_abs)
+    r_dw2 = elem_ratio(dW2.cpu().numpy(), O_or, O_abs)
+    assert r_bt <= ELEM_BT, f"Btilde: an element is off by {r_bt} of sum |alpha_i||dY_i|"
+    assert r_dw2 <= ELEM_DW[dtype_name], f"dW (oracle f, alpha): an element is off by {r_dw2} of |C|^T sum |alpha_i||dY_i|"
     assert torch.equal(dW2, dW3), "pamm_grad is not bit-reproducible"
+    for key, v in (("alpha", r_alpha), ("Btilde", r_bt), ("dW " + dtype_name, max(r_dw, r_dw2))):
+        WORST[key] = max(WORST.get(key, 0.0), v)
+    print(f"[elem] {label}: alpha {r_alpha:.2e}, Btilde {r_bt:.2e}, dW {r_dw:.2e} / {r_dw2:.2e}; worst so far {WORST}", flush=True)
     print(f"[ok]   {label}: f diff {ndiff} (near-ties {nnear}), alpha {e_alpha:.2e}, Btilde {e_bt:.2e}, dW {e_dw:.2e} / {e_dw2:.2e}",
           flush=True)
     return ora, got

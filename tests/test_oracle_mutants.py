@@ -81,8 +81,13 @@ MUTANTS = [
     ("sampler_draws_from_whole_range", "int64_t r = t + (int64_t)bounded(&st, (uint64_t)(b - t));",
      "int64_t r = (int64_t)bounded(&st, (uint64_t)b);",
      [lambda o: sampler_pins.test_matches_the_written_specification(o, 8192, 16, 0), lambda o: sampler_pins.test_every_ordered_draw_equally_likely(o)]),
-    # (dropping the rejection step of the bounded draw cannot be caught by behaviour: for b < 2^31 a rejection happens
-    # with probability below 2^-33 per draw; that line is pinned by the written specification only)
+    ("bounded_draw_without_rejection", "} while (x < reject_below);", "} while (0);",
+     [lambda o: sampler_pins.test_bounded_draw_on_the_published_stream(o, 3 << 62),
+      lambda o: sampler_pins.test_bounded_draw_is_uniform_where_a_plain_remainder_is_not(o)]),
+    ("bounded_draw_rejects_the_wrong_end", "} while (x < reject_below);", "} while (x > 0ULL - reject_below - 1ULL);",
+     [lambda o: sampler_pins.test_bounded_draw_on_the_published_stream(o, 3 << 62)]),
+    ("bounded_draw_threshold_not_reduced", "uint64_t reject_below = (0ULL - u) % u;", "uint64_t reject_below = (0ULL - u);",
+     [lambda o: sampler_pins.test_bounded_draw_on_the_published_stream(o, (1 << 62) + 1)]),
     ("sampler_forgets_the_exchange", "a[r] = tmp;", "a[r] = a[r];",
      [lambda o: sampler_pins.test_full_draw_is_a_permutation(o, 64), lambda o: sampler_pins.test_distinct_in_range_deterministic_prefix(o, 100, 17)]),
     ("bf16_decoded_from_low_half", "uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;",

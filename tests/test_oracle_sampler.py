@@ -1,4 +1,4 @@
-"""Pins for the oracle's generator sampler (Alg. 1, Compress: "sample indices uniformly without replacement").
+"""Pins for the oracle's generator sampler (Alg. 1, Compress, sampling step: k distinct rows, uniform).
 
 The paper fixes only the distribution, so the pins are: the published splitmix64
 vectors, the permutation property at k = b, and the uniform-without-replacement
@@ -73,6 +73,43 @@ def test_miss_probability_matches_hypergeometric(oracle):
     miss = sum(1 for seed in range(trials) if target.isdisjoint(oracle.sample(b, k, 1_000_003 * seed + 17).tolist()))
     p = math.comb(b - s, k) / math.comb(b, k)
     assert abs(miss / trials - p) < 6 * math.sqrt(p * (1 - p) / trials)
+
+
+# ---- the bounded draw and its rejection branch.  The sampler itself only ever asks for ranges below 2^31, where a
+# rejection has probability below 2^-33, so these pins ask for ranges of the order of 2^63, where a quarter to a half
+# of the generator's outputs must be thrown away.
+
+def _published_outputs():
+    return [int(line) for line in open(GOLDEN) if line.strip() and not line.startswith("#")]
+
+
+@pytest.mark.parametrize("u", [3 << 62, (1 << 63) + 12345, (1 << 63) - 1, (1 << 62) + 1, 5, 1])
+def test_bounded_draw_on_the_published_stream(oracle, u):
+    """Expected values come from the published splitmix64 outputs and exact integer arithmetic alone: outputs below
+    2^64 mod u are skipped (each skip consumes one output), the others are reduced mod u."""
+    pub = _published_outputs()
+    cut = (1 << 64) % u
+    want = [x % u for x in pub if x >= cut]
+    if cut > 1 << 61:
+        assert len(want) < len(pub)                   # the published stream really contains rejected outputs for this range
+    got = oracle.bounded(1234567, u, len(want)).tolist()
+    assert got == want
+
+
+def test_bounded_draw_is_uniform_where_a_plain_remainder_is_not(oracle):
+    """Range u = 3 * 2^62: without the rejection the lowest third [0, 2^62) would come up half of the time
+    (2^64 = u + 2^62); with it every third comes up a third of the time."""
+    u, trials = 3 << 62, 60_000
+    draws = oracle.bounded(99, u, trials).astype(object)
+    assert all(0 <= int(v) < u for v in draws[:1000])
+    thirds = Counter(int(v) // (1 << 62) for v in draws)
+    for t in range(3):
+        assert abs(thirds[t] / trials - 1 / 3) < 6 * math.sqrt((1 / 3) * (2 / 3) / trials)
+
+
+def test_bounded_bad_arguments(oracle):
+    with pytest.raises(ValueError):
+        oracle.bounded(0, 0, 4)
 
 
 def _python_restatement(b, k, seed):
