@@ -316,10 +316,13 @@ def test_rows_with_zero_weight_are_left_out(pamm, oracle, k):
             assert rel_fro(got, O) <= TOL_DW["bf16"], (share, rel_fro(got, O))
 
 
-def test_step_can_be_captured_in_a_hip_graph(pamm):
-    """pamm_compress_idx + pamm_grad allocate nothing, never synchronise and record no memset, so a caller can capture
-    them.  Every replay (with eager work and synchronisations in between) must give the eager result bit for bit."""
-    w = workloads.scaled(workloads.WORKLOADS["llama60m"], name="graph", seqs=4, seq_len=300, n=256, m=776, k=24, centres=40)
+@pytest.mark.parametrize("k,seeded", [(24, False), (24, True), (1100, True)], ids=["idx_k24", "seed_k24", "seed_k1100"])
+def test_step_can_be_captured_in_a_hip_graph(pamm, k, seeded):
+    """pamm_compress (seeded: the sampled row numbers ride in the gather kernels' argument blocks, three launches of
+    them at k = 1100) or pamm_compress_idx, followed by pamm_grad: the calls allocate nothing, take no lock, never
+    synchronise and record no memset, so a caller can capture them.  Every replay (with eager work and synchronisations
+    in between) must give the eager result bit for bit."""
+    w = workloads.scaled(workloads.WORKLOADS["llama60m"], name="graph", seqs=4, seq_len=300, n=256, m=776, k=k, centres=40)
     X, dY = workloads.generate(w)
     X, dY = X.cuda(), dY.cuda()
     b, n, m, k = w.b, w.n, w.m, w.k
@@ -331,7 +334,10 @@ def test_step_can_be_captured_in_a_hip_graph(pamm):
     idx = pamm.sample_indices(b, k, 5).cuda()
 
     def step():
-        pamm.compress(X, k, idx=idx, out=out, ws=ws_c)
+        if seeded:
+            pamm.compress(X, k, seed=5, out=out, ws=ws_c)
+        else:
+            pamm.compress(X, k, idx=idx, out=out, ws=ws_c)
         pamm.grad(out.C, out.f, out.alpha, dY, out=dW, ws=ws_g)
 
     step()
