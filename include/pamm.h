@@ -175,6 +175,26 @@ pamm_status pamm_grad_out(const void *C, const int32_t *f, const float *alpha, c
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * pamm_grad for callers that cannot allocate device memory, not even a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Computes exactly what pamm_grad computes (same kernels,
+ * same summation order, bit-identical dW), with the scratch memory taken from a device array of
+ * PAMM_STATIC_SCRATCH_BYTES that is part of the library's image: every GPU the library runs on holds its copy until
+ * the process ends.  The call allocates nothing and frees nothing.
+ *   - Sizes whose pamm_grad_workspace() exceeds PAMM_STATIC_SCRATCH_BYTES are refused with PAMM_ERR_WORKSPACE before
+ *     anything is enqueued (the 1B-shaped layer, b = 65536, n = 2048, m = 6144, k = 128, bf16, needs about 13 MiB).
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents; no part of it has to be
+ *     cleared between calls.  Calls that overlap on one GPU (different streams, or different threads without
+ *     ordering) race on it: order them on one stream.
+ *   - The array's device address is looked up on the first call on each device; make that first call outside
+ *     stream capture.
+ * Arguments as pamm_grad, without (ws, ws_bytes).
+ */
+#define PAMM_STATIC_SCRATCH_BYTES (16u << 20)
+pamm_status pamm_grad_static(const void *C, const int32_t *f, const float *alpha, const void *dY,
+                             int64_t b, int64_t n, int64_t k, int64_t m, pamm_dtype dt,
+                             float *dW, void *stream);
+
+/*
  * Test/benchmark hook: only the contraction stage of ApproxMM.
  *   Btilde out  k x m fp32: Btilde_j = sum_{i: f(i)=j} alpha_i dY_i          (Sec. 3.2, second displayed sum)
  * Same workspace as pamm_grad.

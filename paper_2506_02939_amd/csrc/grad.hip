@@ -11,6 +11,7 @@
 //   k_ctb       dW = C^T Btilde on the matrix cores
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "pamm_device.h"
@@ -1051,6 +1052,43 @@ static pamm_status grad_impl(const void* C, const int32_t* f, const float* alpha
         launch_prep_ctb<F32>(pl, g, C, int(n), int(m), int(k), eta, int(b), dW, out16, m_by_n, s);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
+}
+
+// ---- pamm_grad_static: pamm_grad for callers that cannot allocate.  The scratch memory that pamm_grad takes from its
+// caller (sorted list, per-generator piece ranges, slice histograms, partial rows, the two operands of the product)
+// lives in this file-scope device array instead; every GPU the library runs on holds its own copy at its own address
+// until the process ends.  The array's name is only a host-side stand-in: the address on the current device is looked
+// up once per device with hipGetSymbolAddress and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[PAMM_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static pamm_status static_scratch(void** out) {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return PAMM_ERR_DEVICE;
+    void* p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {          // first call on this device (two first calls at once look up the same address twice: harmless)
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PAMM_ERR_DEVICE;
+        g_scratch_ptr[device].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return PAMM_OK;
+}
+
+extern "C" pamm_status pamm_grad_static(const void* C, const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t n,
+                                        int64_t k, int64_t m, pamm_dtype dt, float* dW, void* stream) {
+    // sizes first: a request that does not fit the array is refused before the device is touched
+    const size_t need = pamm_grad_workspace(b, n, k, m, dt);
+    if (need > size_t(PAMM_STATIC_SCRATCH_BYTES)) return PAMM_ERR_WORKSPACE;
+    void* ws = reinterpret_cast<void*>(uintptr_t(256));          // stands in for the array while the arguments are checked
+    GradPlan pl;
+    pamm_status st = check_grad_args(C, f, alpha, dY, b, n, k, m, dt, PAMM_F32, PAMM_DW_N_BY_M, dW, ws, PAMM_STATIC_SCRATCH_BYTES, &pl);
+    if (st != PAMM_OK) return st;
+    st = static_scratch(&ws);
+    if (st != PAMM_OK) return st;
+    // nothing in the scratch layout has to start at zero: every kernel writes what the next one reads
+    return grad_impl(C, f, alpha, nullptr, dY, b, n, k, m, dt, PAMM_F32, PAMM_DW_N_BY_M, dW, ws, PAMM_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" pamm_status pamm_grad(const void* C, const int32_t* f, const float* alpha, const void* dY, int64_t b, int64_t n,

@@ -23,7 +23,7 @@ PAMM_DW_N_BY_M, PAMM_DW_M_BY_N = 0, 1
 EXPORTS = [
     "pamm_status_string", "pamm_compress_workspace", "pamm_grad_workspace", "pamm_sample_indices",
     "pamm_compress", "pamm_compress_idx", "pamm_compress_eps", "pamm_compress_idx_eps", "pamm_grad", "pamm_grad_eps",
-    "pamm_grad_out", "pamm_contract",
+    "pamm_grad_out", "pamm_grad_static", "pamm_contract",
     "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
     "pamm_debug_set_plan", "pamm_debug_bounded",
 ]
@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.pamm_grad_eps.restype = ci
     lib.pamm_grad_out.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, sz, vp]
     lib.pamm_grad_out.restype = ci
+    lib.pamm_grad_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, vp]
+    lib.pamm_grad_static.restype = ci
     lib.pamm_contract.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_contract.restype = ci
     lib.pamm_profile_begin.argtypes = []
@@ -213,6 +215,20 @@ def grad(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor
         st = lib.pamm_grad_eps(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(eta, "eta"), _dev(dY, "dY"), b, n, k, m, dt,
                                _dev(out, "out"), ws.data_ptr(), ws.numel(), _stream())
         _check(st, "pamm_grad_eps")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def grad_static(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """pamm_grad_static: pamm_grad with the library's own static scratch array; the caller passes inputs and `out`
+    (n x m fp32) only, and nothing is allocated on either side."""
+    k, n = C.shape
+    b, m = dY.shape
+    st = lib.pamm_grad_static(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, _dtype_code(dY),
+                              _dev(out, "out"), _stream())
+    _check(st, "pamm_grad_static")
     return out
 
 
