@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the PAMM hot path on one MI355X: one step = pamm_compress + pamm_grad over one synthetic batch.
 
-Prints ONE JSON line.  `value` is tokens/s = b / (t_compress + t_grad) with X and dY resident in HBM before the
-timed region; consecutive steps rotate through `--sets` copies of the inputs so that a step finds none of its
-inputs in the Infinity Cache.  `roofline` covers the dominant kernel (k_contract, the single pass over dY): algorithmic bytes per
-launch divided by its mean duration, the latter measured here with HIP events on the launch stream (the library's
-own per-kernel event hooks) over a second run of the same K steps.  `cpu_baseline` is the fp64 oracle timed on
-this machine's host cores on the same batch.  `exact_gemm` is the plain X^T dY product (vendor BLAS through
-torch.matmul) on the same GPU, for scale only.
+Prints ONE JSON line.  `value` is tokens/s = b / (t_compress + t_grad) on the headline workload (the 1B-shaped layer)
+with X and dY resident in HBM before the timed region; consecutive steps rotate through `--sets` copies of the inputs
+so that a step finds none of its inputs in the Infinity Cache.  `roofline` covers the dominant kernel (k_contract, the
+single pass over dY): algorithmic bytes per launch divided by its mean duration, the latter measured here with HIP
+events on the launch stream (the library's own per-kernel event hooks) over a second run of the same K steps;
+`roofline_kernels` gives the same figures for all three hot kernels (score, contraction, small product), against the
+HBM peak and, where the kernel is a matrix product that outruns its bytes, against the bf16 matrix peak.  `configs`
+carries every workload of the benchmark's configuration list (median step time, per-kernel durations and roofline
+fractions, counter traffic from profiles/), each timed like the headline over `--config-steps` steps.
+`cpu_baseline` is the fp64 oracle timed on this machine's host cores on the headline batch.  `exact_gemm` is the
+plain X^T dY product (vendor BLAS through torch.matmul) on the same GPU, for scale only.
 """
 from __future__ import annotations
 
@@ -23,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_PEAK_BF16_TFLOPS = 2500.0
+FP32_MATRIX_PEAK_TFLOPS = 157.3
 
 
 def algorithmic_bytes(w, piece_rows_overhead=0):
@@ -36,6 +41,11 @@ def algorithmic_bytes(w, piece_rows_overhead=0):
     }
 
 
+def algorithmic_flops(w):
+    """Multiply-adds x 2 of the two matrix products of the path (App. J counts the same products)."""
+    return {"k_score": 2.0 * w.b * w.k * w.n, "k_ctb": 2.0 * w.k * w.n * w.m}
+
+
 def read_traffic(workload: str, kernel: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), from the committed summary."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.md")
@@ -45,6 +55,100 @@ def read_traffic(workload: str, kernel: str):
         return None
     mt = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
     return float(mt.group(1)) if mt else None
+
+
+def kernel_table(w, per_kernel_us):
+    """Per kernel: average duration, algorithmic rate against the HBM peak, matrix rate against the bf16 MFMA peak."""
+    alg, flops = algorithmic_bytes(w), algorithmic_flops(w)
+    peak_tf = MFMA_PEAK_BF16_TFLOPS if w.dtype == "bf16" else FP32_MATRIX_PEAK_TFLOPS
+    out = {}
+    for name, us in per_kernel_us.items():
+        ent = {"avg_us": round(us, 2)}
+        if name in alg:
+            gbs = alg[name] / (us * 1e-6) / 1e9
+            ent["algorithmic_bytes"] = alg[name]
+            ent["algorithmic_GBps"] = round(gbs, 1)
+            ent["frac_of_hbm_peak"] = round(gbs / HBM_PEAK_GBS, 4)
+            ent["traffic"] = read_traffic(w.name, name)
+        if name in flops:
+            tf = flops[name] / (us * 1e-6) / 1e12
+            ent["TFLOPs"] = round(tf, 1)
+            ent["frac_of_matrix_peak"] = round(tf / peak_tf, 4)
+            # which roof is nearer: the time the bytes need at the HBM peak against the time the flops need at the matrix peak
+            ent["bound"] = "mfma" if flops[name] / (peak_tf * 1e12) > alg[name] / (HBM_PEAK_GBS * 1e9) else "hbm"
+        elif name in alg:
+            ent["bound"] = "hbm"
+        out[name] = ent
+    return out
+
+
+def time_workload(torch, pamm, workloads, name, steps, warmup, nsets, eps=None, dw="f32", dw_transposed=False):
+    """K timed steps of compress + grad on one workload.  Returns (record, tensors kept for the optional extra legs)."""
+    w = workloads.WORKLOADS[name]
+    X_cpu, dY_cpu = workloads.generate(w)
+    Xs = [X_cpu.cuda() for _ in range(nsets)]
+    dYs = [dY_cpu.cuda() for _ in range(nsets)]
+    b, n, m, k = w.b, w.n, w.m, w.k
+    dt = pamm.PAMM_BF16 if w.dtype == "bf16" else pamm.PAMM_F32
+    out = pamm.Compressed(torch.empty(k, n, dtype=Xs[0].dtype, device="cuda"), torch.empty(b, dtype=torch.int32, device="cuda"),
+                          torch.empty(b, dtype=torch.float32, device="cuda"))
+    dw_kw = {}
+    if dw != "f32" or dw_transposed:
+        dw_kw = dict(out_dtype=torch.bfloat16 if dw == "bf16" else torch.float32, transposed=dw_transposed)
+    dW = torch.empty((m, n) if dw_transposed else (n, m), dtype=dw_kw.get("out_dtype", torch.float32), device="cuda")
+    ws_c = torch.empty(pamm.compress_workspace(b, n, k, dt), dtype=torch.uint8, device="cuda")
+    ws_g = torch.empty(pamm.grad_workspace(b, n, k, m, dt), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        pamm.compress(Xs[i % nsets], k, seed=i, eps=eps, out=out, ws=ws_c)      # fresh generators every step, as in training (App. F)
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g, **dw_kw)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    # every step on its own (events on the current stream, which is the stream the kernels are launched on):
+    # the median step, and the split between the two calls
+    reps = max(1, min(steps, 100))
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+    for i in range(reps):
+        ev[i][0].record()
+        pamm.compress(Xs[i % nsets], k, seed=i, eps=eps, out=out, ws=ws_c)
+        ev[i][1].record()
+        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g, **dw_kw)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    tcs = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    tgs = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    tot = sorted(e[0].elapsed_time(e[2]) for e in ev)
+    med = lambda v: v[len(v) // 2]
+
+    # per-kernel durations: the same K steps again with the library's event hooks on
+    pamm.profile_begin()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    prof = pamm.profile_end()
+    per_kernel_us = {kname: 1e3 * ms / cnt for kname, (ms, cnt) in prof.items()}
+    launches = sum(cnt for _, cnt in prof.values()) / steps
+
+    rec = {
+        "workload": w.name, "b": b, "n": n, "m": m, "k": k, "dtype": w.dtype, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(med(tot), 4),
+        "tokens_per_s": round(b / (ms_per_step * 1e-3), 1),
+        "ms_compress": round(med(tcs), 4), "ms_grad": round(med(tgs), 4), "launches_per_step": round(launches, 2),
+        "kernels": kernel_table(w, per_kernel_us),
+    }
+    return rec, dict(w=w, X_cpu=X_cpu, dY_cpu=dY_cpu, X=Xs[0], dY=dYs[0], per_kernel_us=per_kernel_us)
+
+
+ALL_WORKLOADS = ["tiny", "llama60m", "llama350m", "llama1b", "llama7b_k32", "llama7b_k256", "llama7b_k1024"]
 
 
 def main() -> int:
@@ -64,6 +168,8 @@ def main() -> int:
     ap.add_argument("--layer", action="store_true",
                     help="also time the forward + backward pass of the linear layer of Alg. 2-3 (exact products through the "
                          "vendor BLAS) against the same layer with the exact weight gradient; adds a \"layer\" object")
+    ap.add_argument("--no-configs", action="store_true", help="time the headline workload only (no \"configs\" array)")
+    ap.add_argument("--config-steps", type=int, default=100, help="timed steps for each entry of the \"configs\" array")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -80,95 +186,39 @@ def main() -> int:
         return 3
     from paper_2506_02939_amd import pamm, workloads
 
-    w = workloads.WORKLOADS[args.workload]
-    X_cpu, dY_cpu = workloads.generate(w)
     nsets = max(1, args.sets)
-    Xs = [X_cpu.cuda() for _ in range(nsets)]
-    dYs = [dY_cpu.cuda() for _ in range(nsets)]
-    X, dY = Xs[0], dYs[0]
+    rec, kept = time_workload(torch, pamm, workloads, args.workload, args.steps, args.warmup, nsets, eps=args.eps, dw=args.dw,
+                              dw_transposed=args.dw_transposed)
+    w, X, dY, X_cpu, dY_cpu = kept["w"], kept["X"], kept["dY"], kept["X_cpu"], kept["dY_cpu"]
     b, n, m, k = w.b, w.n, w.m, w.k
-    dt = pamm.PAMM_BF16 if w.dtype == "bf16" else pamm.PAMM_F32
+    kernels = rec["kernels"]
 
-    out = pamm.Compressed(torch.empty(k, n, dtype=X.dtype, device="cuda"), torch.empty(b, dtype=torch.int32, device="cuda"),
-                          torch.empty(b, dtype=torch.float32, device="cuda"))
-    dw_kw = {}
-    if args.dw != "f32" or args.dw_transposed:
-        dw_kw = dict(out_dtype=torch.bfloat16 if args.dw == "bf16" else torch.float32, transposed=args.dw_transposed)
-    dW = torch.empty((m, n) if args.dw_transposed else (n, m), dtype=dw_kw.get("out_dtype", torch.float32), device="cuda")
-    ws_c = torch.empty(pamm.compress_workspace(b, n, k, dt), dtype=torch.uint8, device="cuda")
-    ws_g = torch.empty(pamm.grad_workspace(b, n, k, m, dt), dtype=torch.uint8, device="cuda")
-
-    def step(i):
-        pamm.compress(Xs[i % nsets], k, seed=i, eps=args.eps, out=out, ws=ws_c)      # fresh generators every step, as in training (App. F)
-        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g, **dw_kw)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    # separate timing of the two calls (events on the current stream)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    tc = tg = 0.0
-    reps = max(1, min(args.steps, 50))
-    for i in range(reps):
-        ev[0].record()
-        pamm.compress(Xs[i % nsets], k, seed=i, eps=args.eps, out=out, ws=ws_c)
-        ev[1].record()
-        pamm.grad(out.C, out.f, out.alpha, dYs[i % nsets], eta=out.eta, out=dW, ws=ws_g, **dw_kw)
-        ev[2].record()
-        torch.cuda.synchronize()
-        tc += ev[0].elapsed_time(ev[1])
-        tg += ev[1].elapsed_time(ev[2])
-    tc, tg = tc / reps, tg / reps
-
-    # per-kernel durations: the same K steps again with the library's event hooks on
-    pamm.profile_begin()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    prof = pamm.profile_end()
-    per_kernel_us = {name: 1e3 * ms / cnt for name, (ms, cnt) in prof.items()}
-
-    alg = algorithmic_bytes(w)
     dom = "k_contract"
-    dur_s = per_kernel_us[dom] * 1e-6
-    achieved = alg[dom] / dur_s / 1e9
     roofline = {
-        "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(w.name, dom),
-        "algorithmic_bytes_per_launch": alg[dom], "avg_launch_us": round(per_kernel_us[dom], 2),
+        "kernel": dom, "bound": "hbm", "achieved": kernels[dom]["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": kernels[dom]["traffic"],
+        "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes"], "avg_launch_us": kernels[dom]["avg_us"],
     }
-    kernels = {}
-    for name, us in per_kernel_us.items():
-        ent = {"avg_us": round(us, 2)}
-        if name in alg:
-            ent["algorithmic_GBps"] = round(alg[name] / (us * 1e-6) / 1e9, 1)
-            ent["frac_of_hbm_peak"] = round(alg[name] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
-        if name == "k_score":
-            ent["TFLOPs"] = round(2.0 * b * k * n / (us * 1e-6) / 1e12, 1)
-        if name == "k_ctb":
-            ent["TFLOPs"] = round(2.0 * k * n * m / (us * 1e-6) / 1e12, 1)
-        kernels[name] = ent
+    hot = {name: kernels[name] for name in ("k_score", "k_contract", "k_ctb") if name in kernels}
 
     result = {
-        "metric": "PAMM compress+grad tokens/s", "value": round(b / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "metric": "PAMM compress+grad tokens/s", "value": rec["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rec["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "b": b, "n": n, "m": m, "k": k, "dtype": w.dtype,
                    "recipe": f"{w.centres} centres, sigma {w.sigma}, {w.structure}, pad {w.pad_frac}",
                    "input_sets_rotated": nsets, "eps": args.eps,
-                   "dW": args.dw + (" m x n" if args.dw_transposed else " n x m")},
-        "ms_compress": round(tc, 4), "ms_grad": round(tg, 4),
+                   "dW": args.dw + (" m x n" if args.dw_transposed else " n x m"),
+                   "Btilde": "bf16 operand of the C^T Btilde product (rounded once from fp32 sums)" if w.dtype == "bf16" else "fp32"},
+        "ms_per_step_median": rec["ms_per_step_median"],
+        "ms_compress": rec["ms_compress"], "ms_grad": rec["ms_grad"], "launches_per_step": rec["launches_per_step"],
         "roofline": roofline,
+        "roofline_kernels": hot,
+        "min_hbm_bound_frac": min((v["frac_of_hbm_peak"] for v in hot.values() if v.get("bound") == "hbm"), default=None),
         "kernels": kernels,
     }
+    del kept
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -239,6 +289,19 @@ def main() -> int:
             "sample": f"the full {w.name} batch ({b} tokens), best of {reps_cpu} repetitions: "
                       f"compress {best[1]:.2f} s + grad {best[2]:.2f} s",
         }
+
+    if not args.no_configs:
+        # every workload of the configuration list, timed like the headline (no oracle leg: that runs once, above)
+        configs = []
+        for name in ALL_WORKLOADS:
+            if name == w.name and args.eps is None and args.dw == "f32" and not args.dw_transposed:
+                configs.append({key: rec[key] for key in rec})
+                continue
+            torch.cuda.empty_cache()
+            r, kept_c = time_workload(torch, pamm, workloads, name, args.config_steps, min(args.warmup, 10), nsets)
+            del kept_c
+            configs.append(r)
+        result["configs"] = configs
 
     print(json.dumps(result), flush=True)
     return 0
