@@ -5,10 +5,13 @@
 // Launches on the caller's stream:
 //   k_gather    C_j = X[idx_j] (bit copy), ||C_j||^2 in fp64, a content hash per generator (k_gather_arg: the same
 //               with up to 512 sampled row numbers in the kernel's argument block)
-//   k_score     streams X once; D = C X^T on the matrix cores with C staged through LDS, then per token the
-//               largest values of s(i,j) = <X_i,C_j>^2/||C_j||^2 (Lemma 1) and where they occur.  With up to 256
-//               generators (one column block) it also takes the final decision: f, alpha (Eq. 1), the few rows
-//               whose leading scores are too close for fp32 to separate being re-decided in fp64
+//   k_dedupe    only with more than 256 generators: 1/||C_j|| per generator, 0 for those that can never win (zero
+//               rows, and bit-identical copies of a lower-numbered generator: lowest j wins a tie by definition)
+//   k_score     streams X once; D = C X^T on the matrix cores with C staged through LDS, then per token the largest
+//               and second largest |<X_i,C_j>| / ||C_j|| (the square root of the score of Lemma 1) straight from the
+//               accumulator registers.  With up to 256 generators (one column block) it also takes the final
+//               decision: f, alpha (Eq. 1), the few rows whose leading scores are too close for fp32 to separate
+//               being re-decided in fp64 by the wave that owns them
 //   k_finalize  only with more than 256 generators: merges the column blocks and takes that final decision
 #include <hip/hip_runtime.h>
 
@@ -19,63 +22,41 @@
 namespace pamm {
 
 // ------------------------------------------------------------------------------------------------
-// Per-token record of the leading scores.  s1 > s2 > s3 > s4 are the four largest DISTINCT score values known;
-// j1 / j2 / j3 are the lowest generator numbers attaining s1 / s2 / s3 (j3 = -1: the third value is known but not
-// who attains it; s4 is a value only); d1 is the dot product behind s1; jt is the lowest generator other than j1
-// that attains s1 exactly (-1 if none).  Bit-identical generators (padding tokens sampled twice) produce
-// bit-identical scores, so they meet in jt instead of hiding the real runners-up.
-struct Best {
-    float s1; int j1; float d1; int jt; float s2; int j2; float s3; int j3; float s4;
+// What the score kernel keeps of a token after its pass over one column block.  With r(i,j) = |<X_i,C_j>| / ||C_j||
+// (r^2 is the score <X_i,C_j>^2 / ||C_j||^2 of Lemma 1, so both have the same argmax):
+//   m1   the largest r over the block's generators,  j1 the lowest generator attaining it,
+//   a1   <X_i,C_j1> / ||C_j1|| with its sign (alpha_i = a1 / ||C_j1||, Eq. 1),
+//   m2   the second largest r (equal to m1 when two generators attain it).
+// Generators that can never win are left out by giving them the factor 1/||C_j|| = 0: zero rows, and bit-identical
+// copies of a lower-numbered generator (padding tokens sampled twice; the lowest j wins a tie by definition).
+// A token whose m2 is within kBand (relative) of m1 cannot be decided in fp32: the generators within the band are
+// named (up to kMaxNamed of them) and the decision among them is taken again in fp64.
+constexpr int kMaxNamed = 6;              // named candidates per token and column block
+constexpr int kTooMany = kMaxNamed + 1;   // more than that: every generator is evaluated again
+constexpr float kBand = 0x1.2p-13f;       // on r; about 2^-12 on the score r^2
 
-    __device__ __forceinline__ void init() {
-        s1 = -1.f; j1 = 0; d1 = 0.f; jt = -1; s2 = -2.f; j2 = 0; s3 = -3.f; j3 = -1; s4 = -4.f;
-    }
+// 32-byte record per token and column block (several column blocks only): generator numbers fit 16 bits (k <= 16384)
+struct BlockRecord {
+    float m1, a1;
+    int j1, cnt;                 // cnt: 0 = nobody else within the band, 1..kMaxNamed = names[] (j1 among them), kTooMany
+    int names[kMaxNamed];
 
-    // A value below s1; j = -1 if it is not known who attains it.  Such a value never ranks second: in the record it
-    // comes from, two larger values stand above it.
-    __device__ __forceinline__ void insert_lower(float s, int j) {
-        if (s > s2) { s4 = s3; s3 = s2; j3 = j2; s2 = s; j2 = j; }
-        else if (s == s2) { if (j >= 0) j2 = min(j2, j); }
-        else if (s > s3) { s4 = s3; s3 = s; j3 = j; }
-        else if (s == s3) { j3 = (j3 < 0 || j < 0) ? max(j3, j) : min(j3, j); }
-        else if (s > s4) { s4 = s; }
+    __device__ __forceinline__ void store(u32x4_t* dst, float nx) const {
+        dst[0] = u32x4_t{__float_as_uint(m1), __float_as_uint(a1), uint32_t(j1) | (uint32_t(cnt) << 16),
+                         uint32_t(names[0]) | (uint32_t(names[1]) << 16)};
+        dst[1] = u32x4_t{uint32_t(names[2]) | (uint32_t(names[3]) << 16), uint32_t(names[4]) | (uint32_t(names[5]) << 16),
+                         __float_as_uint(nx), 0u};
     }
-
-    // union with a record built over a disjoint set of generators
-    __device__ __forceinline__ void merge(const Best& o) {
-        if (o.s1 > s1) {
-            s4 = s3; s3 = s2; j3 = j2; s2 = s1; j2 = j1;
-            s1 = o.s1; j1 = o.j1; d1 = o.d1; jt = o.jt;
-        } else if (o.s1 == s1) {
-            int lo = min(j1, o.j1), t = max(j1, o.j1);
-            if (o.j1 < j1) d1 = o.d1;
-            if (jt >= 0) t = min(t, jt);
-            if (o.jt >= 0) t = min(t, o.jt);
-            j1 = lo; jt = t;
-        } else {
-            insert_lower(o.s1, o.j1);
-        }
-        insert_lower(o.s2, o.j2);
-        insert_lower(o.s3, o.j3);
-        if (o.s4 < s3 && o.s4 > s4) s4 = o.s4;      // three larger values of o are already in: at best fourth
+    __device__ __forceinline__ void load_lead(const u32x4_t* src) {
+        const u32x4_t p = src[0];
+        m1 = __uint_as_float(p.x); a1 = __uint_as_float(p.y); j1 = int(p.z & 0xffffu); cnt = int(p.z >> 16);
+        names[0] = int(p.w & 0xffffu); names[1] = int(p.w >> 16);
     }
-
-    // 32-byte record: generator numbers fit 16 bits (k <= 16384); 0xffff stands for "none"
-    __device__ __forceinline__ void store(u32x4_t* dst) const {
-        dst[0] = u32x4_t{__float_as_uint(s1), __float_as_uint(d1), __float_as_uint(s2), __float_as_uint(s3)};
-        dst[1] = u32x4_t{__float_as_uint(s4), uint32_t(j1) | (uint32_t(jt) << 16), uint32_t(j2) | (uint32_t(j3) << 16), 0u};
+    __device__ __forceinline__ void load_rest(const u32x4_t* src) {
+        const u32x4_t q = src[1];
+        names[2] = int(q.x & 0xffffu); names[3] = int(q.x >> 16); names[4] = int(q.y & 0xffffu); names[5] = int(q.y >> 16);
     }
-    static __device__ __forceinline__ void store_norm(u32x4_t* dst, float nx) {      // ||X_i||^2 rides in the spare slot
-        reinterpret_cast<float*>(dst + 1)[3] = nx;
-    }
-    static __device__ __forceinline__ float load_norm(const u32x4_t* src) { return __uint_as_float(src[1].w); }
-    __device__ __forceinline__ void load(const u32x4_t* src) {
-        const u32x4_t p = src[0], q = src[1];
-        s1 = __uint_as_float(p.x); d1 = __uint_as_float(p.y); s2 = __uint_as_float(p.z); s3 = __uint_as_float(p.w);
-        s4 = __uint_as_float(q.x);
-        j1 = int(q.y & 0xffffu); jt = int(q.y >> 16); jt = jt == 0xffff ? -1 : jt;
-        j2 = int(q.z & 0xffffu); j3 = int(q.z >> 16); j3 = j3 == 0xffff ? -1 : j3;
-    }
+    static __device__ __forceinline__ float load_norm(const u32x4_t* src) { return __uint_as_float(src[1].z); }
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -87,7 +68,7 @@ struct IdxByValue { int32_t v[kArgGenerators]; };
 
 template <typename TR>
 __device__ __forceinline__ void gather_row(const u32x4_t* __restrict__ X, int j, int src, int b, int nch, u32x4_t* __restrict__ C,
-                                           int32_t* __restrict__ idx_out, float* __restrict__ inv, double* __restrict__ cn2,
+                                           int32_t* __restrict__ idx_out, float* __restrict__ rn, double* __restrict__ cn2,
                                            unsigned long long* __restrict__ hash, int32_t* __restrict__ eta) {
     if (eta && j == 0 && threadIdx.x == 0) *eta = 0;          // rows dropped by the neighbourhood condition: counted later
     src = src < 0 ? 0 : (src >= b ? b - 1 : src);
@@ -119,7 +100,7 @@ __device__ __forceinline__ void gather_row(const u32x4_t* __restrict__ X, int j,
     if (threadIdx.x == 0) {
         double t = (sacc[0] + sacc[1]) + (sacc[2] + sacc[3]);
         cn2[j] = t;
-        inv[j] = t > 0.0 ? float(1.0 / t) : 0.f;
+        rn[j] = t > 0.0 ? float(1.0 / sqrt(t)) : 0.f;      // 1/||C_j||; a zero row can never win (copies: see k_dedupe)
         hash[j] = sh[0] + sh[1] + sh[2] + sh[3];
         idx_out[j] = src;
     }
@@ -127,30 +108,54 @@ __device__ __forceinline__ void gather_row(const u32x4_t* __restrict__ X, int j,
 
 template <typename TR>
 __global__ __launch_bounds__(256) void k_gather(const u32x4_t* __restrict__ X, const int32_t* __restrict__ idx_in, int b, int nch,
-                                                u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
+                                                u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ rn,
                                                 double* __restrict__ cn2, unsigned long long* __restrict__ hash,
                                                 int32_t* __restrict__ eta) {
-    gather_row<TR>(X, blockIdx.x, idx_in[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
+    gather_row<TR>(X, blockIdx.x, idx_in[blockIdx.x], b, nch, C, idx_out, rn, cn2, hash, eta);
 }
 
 // generators j0 .. j0 + gridDim.x - 1, their row numbers in the argument block
 template <typename TR>
 __global__ __launch_bounds__(256) void k_gather_arg(const u32x4_t* __restrict__ X, const IdxByValue idx_in, int j0, int b, int nch,
-                                                    u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ inv,
+                                                    u32x4_t* __restrict__ C, int32_t* __restrict__ idx_out, float* __restrict__ rn,
                                                     double* __restrict__ cn2, unsigned long long* __restrict__ hash,
                                                     int32_t* __restrict__ eta) {
-    gather_row<TR>(X, j0 + blockIdx.x, idx_in.v[blockIdx.x], b, nch, C, idx_out, inv, cn2, hash, eta);
+    gather_row<TR>(X, j0 + blockIdx.x, idx_in.v[blockIdx.x], b, nch, C, idx_out, rn, cn2, hash, eta);
 }
 
 // ------------------------------------------------------------------------------------------------
-// The final word on f(i) and alpha_i.  A token whose leading scores are within 2^-12 (relative) of each other is
-// re-decided in fp64: among up to four named candidates (the winner, a non-identical generator that ties with it
-// exactly, the runners-up) when every value that close has a name, among all generators otherwise (in the
-// workloads here: never seen; three values that close: one token in 250 000).  Such tokens are rare but unevenly
-// spread, so a workgroup pools them in an LDS queue (decide_or_queue, called by every lane for its token) and its
-// waves then share them out (drain_queue, called by the whole workgroup).
-constexpr int kRedoInts = 6;     // row, number of extra candidates (4 = all generators), j1, c1, c2, c3
+// k_dedupe: for the shapes with several column blocks (with one block the score kernel does this itself), rn[j] <- 0
+// for every generator whose row is a bit-identical copy of a lower-numbered one (same content hash, same fp64 norm):
+// it can never win, lowest j takes a tie.  64 generators per workgroup, four threads each, which share the
+// comparisons with the lower-numbered generators; their (hash, norm) pairs pass through LDS in tiles of 256.
+__global__ __launch_bounds__(256) void k_dedupe(const double* __restrict__ cn2, const unsigned long long* __restrict__ hash, int k,
+                                                float* __restrict__ rn) {
+    typedef __attribute__((ext_vector_type(2))) unsigned long long u64x2_t;
+    __shared__ u64x2_t tile[256];
+    __shared__ int copy_of_lower[64];
+    const int tid = threadIdx.x, part = tid >> 6;
+    const int j = blockIdx.x * 64 + (tid & 63), jj = min(j, k - 1);
+    const u64x2_t mine = {hash[jj], (unsigned long long)__double_as_longlong(cn2[jj])};
+    if (tid < 64) copy_of_lower[tid] = 0;
+    bool copy = false;
+    for (int t0 = 0; t0 < int(blockIdx.x) * 64 + 64; t0 += 256) {
+        const int src = min(t0 + tid, k - 1);
+        __syncthreads();
+        tile[tid] = u64x2_t{hash[src], (unsigned long long)__double_as_longlong(cn2[src])};
+        __syncthreads();
+        const int lim = min(256, j - t0);                      // only generators below j count
+#pragma unroll 8
+        for (int q = part; q < lim; q += 4) {
+            const u64x2_t o = tile[q];
+            copy |= (o.x == mine.x) & (o.y == mine.y);
+        }
+    }
+    if (copy) copy_of_lower[tid & 63] = 1;
+    __syncthreads();
+    if (tid < 64 && j < k && copy_of_lower[tid]) rn[j] = 0.f;
+}
 
+// ------------------------------------------------------------------------------------------------
 // Neighbourhood condition (Eq. 2): ||X_i - alpha_i C_f(i)||_2 <= eps ||X_i||_2, i.e. s(i,f(i)) >= (1 - eps^2) ||X_i||^2
 // (the residual of a projection: ||X_i||^2 - s).  keep = 1 - eps^2; keep < 0 switches the test off (eps >= 1 can
 // drop nothing).  In fp32 the test is trusted outside a band of 2^-11 ||X_i||^2 around the limit; inside it the
@@ -159,6 +164,16 @@ constexpr int kRedoInts = 6;     // row, number of extra candidates (4 = all gen
 struct Neighbourhood {
     double keep;           // 1 - eps^2, or negative: no condition
     int* dropped;          // LDS counter of the workgroup
+
+    // fp32 verdict on a token whose best score is s1 = m1^2: sure to be dropped / too close to call
+    __device__ __forceinline__ void judge(float m1, float nx, bool& drop, bool& unsure) const {
+        drop = unsure = false;
+        if (keep >= 0.0) {
+            const float s1 = m1 * m1, lim = float(keep) * nx, band = 0x1p-11f * nx;
+            drop = s1 < lim - band;
+            unsure = !drop && s1 < lim + band;
+        }
+    }
 };
 
 // Dot products of one row of X with two generators, in fp64, by the whole wave.  This code runs a handful of times
@@ -196,93 +211,41 @@ __device__ __noinline__ void wave_dot2(const u32x4_t* __restrict__ x, const u32x
     db = wave_sum(acc1);
 }
 
-// Called by every lane.  Writes f and alpha of the lane's token unless it needs a second look; then it is queued.
-__device__ __forceinline__ void decide_or_queue(const float* __restrict__ inv, const double* __restrict__ cn2,
-                                                const unsigned long long* __restrict__ hash, bool valid, int row, const Best& st,
-                                                float nx, const Neighbourhood& nb, int32_t* __restrict__ f,
-                                                float* __restrict__ alpha, int* q_count, int* q_entries) {
-    if (!valid) return;
-    bool unsure = false, drop = false;
-    if (nb.keep >= 0.0) {
-        const float lim = float(nb.keep) * nx, band = 0x1p-11f * nx;
-        drop = st.s1 < lim - band;
-        unsure = !drop && st.s1 < lim + band;
-    }
-    int ncand = 0, c1 = 0, c2 = 0, c3 = 0;
-    if (st.s1 > 0.f) {
-        const float thr = st.s1 * (1.f - 0x1p-12f);
-        // an exact tie between two generators whose rows are bit-identical needs no second look: the lower one wins
-        if (st.jt >= 0 &&
-            !(hash[st.j1] == hash[st.jt] && __double_as_longlong(cn2[st.j1]) == __double_as_longlong(cn2[st.jt])))
-            c1 = st.jt, ncand = 1;
-        if (st.s2 >= thr) { (ncand == 0 ? c1 : c2) = st.j2; ++ncand; }
-        if (st.s3 >= thr) {
-            if (st.j3 >= 0) { (ncand == 0 ? c1 : (ncand == 1 ? c2 : c3)) = st.j3; ++ncand; }
-            else ncand = 4;
-        }
-        if (st.s4 >= thr) ncand = 4;
-    }
-    if (ncand == 0 && !unsure) {
-        f[row] = st.j1;
-        alpha[row] = drop ? 0.f : st.d1 * inv[st.j1];
-        if (drop) atomicAdd(nb.dropped, 1);
-    } else {
-        int* e = q_entries + atomicAdd(q_count, 1) * kRedoInts;
-        e[0] = row; e[1] = ncand; e[2] = st.j1; e[3] = c1; e[4] = c2; e[5] = c3;
-    }
-}
-
-// Called by the whole workgroup (NWAVES waves) after a barrier that follows the last decide_or_queue.
-template <typename TR, int NWAVES>
-__device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                            const double* __restrict__ cn2, int nch, int k, const Neighbourhood& nb,
-                                            int32_t* __restrict__ f, float* __restrict__ alpha, const int* q_count,
-                                            const int* q_entries) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int total = *q_count;
-    for (int t = wave; t < total; t += NWAVES) {
-        const int* e = q_entries + t * kRedoInts;
-        const int row = e[0], rn = e[1];
-        const u32x4_t* xr = X + size_t(row) * nch;
-        double bs = -1.0, bd = 0.0, bc = 1.0;
-        int bj = 0;
-        auto take = [&](int j, double d, double c2n) {
-            const double sc = c2n > 0.0 ? d * d / c2n : 0.0;
-            if (sc > bs) { bs = sc; bd = d; bc = c2n; bj = j; }                   // strict: lowest j keeps a tie
-        };
-        auto eval2 = [&](int ja, int jb) {                     // ja <= jb; ja == jb evaluates one generator
-            const double na = cn2[ja], nb = cn2[jb];          // in flight together with the rows
-            double da, db;
-            wave_dot2<TR>(xr, C + size_t(ja) * nch, C + size_t(jb) * nch, nch, da, db);
-            take(ja, da, na);
-            if (jb != ja) take(jb, db, nb);
-        };
-        if (rn == 0) {
-            eval2(e[2], e[2]);             // only the neighbourhood condition is in doubt
-        } else if (rn < 4) {
-            // the named candidates in increasing j; unused slots sort to the end
-            constexpr int kNone = 0x7fffffff;
-            int a0 = e[2], a1 = e[3], a2 = rn >= 2 ? e[4] : kNone, a3 = rn >= 3 ? e[5] : kNone;
-            auto cx = [](int& x, int& y) { const int lo = min(x, y), hi = max(x, y); x = lo; y = hi; };
-            cx(a0, a1); cx(a2, a3); cx(a0, a2); cx(a1, a3); cx(a1, a2);
-            eval2(a0, a1);
-            if (rn == 2) eval2(a2, a2);
-            if (rn == 3) eval2(a2, a3);
-        } else {
+// The final word on one token, by one whole wave, in fp64: the best of its candidates by the score d^2 / ||C_j||^2
+// (lowest j on a tie), then the neighbourhood condition, then f and alpha.  The candidates are every generator when
+// `all` is set, else names[0..n) (a list in LDS, in any order), or the single generator j_single when names is null.
+template <typename TR>
+__device__ __noinline__ void second_look(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
+                                         const double* __restrict__ cn2, int nch, int k, int row, const int* names, int n, bool all,
+                                         int j_single, Neighbourhood nb, int32_t* __restrict__ f, float* __restrict__ alpha) {
+    const u32x4_t* xr = X + size_t(row) * nch;
+    const int count = all ? k : (names ? n : 1);
+    double bs = -1.0, bd = 0.0, bc = 1.0;
+    int bj = 0;
+    auto take = [&](int j, double d, double c2n) {
+        const double sc = c2n > 0.0 ? d * d / c2n : 0.0;
+        if (sc > bs || (sc == bs && j < bj)) { bs = sc; bd = d; bc = c2n; bj = j; }
+    };
+    auto cand = [&](int q) { return all ? q : (names ? names[q] : j_single); };
 #pragma unroll 1
-            for (int j0 = 0; j0 < k; j0 += 2) eval2(j0, min(j0 + 1, k - 1));
-        }
-        bool kept = true;
-        if (nb.keep >= 0.0) {
-            double nx, unused;
-            wave_dot2<TR>(xr, xr, xr, nch, nx, unused);
-            kept = bd * bd >= nb.keep * nx * bc;
-        }
-        if (lane == 0) {
-            f[row] = bj;
-            alpha[row] = (kept && bc > 0.0) ? float(bd / bc) : 0.f;
-            if (!kept) atomicAdd(nb.dropped, 1);
-        }
+    for (int q = 0; q < count; q += 2) {
+        const int ja = cand(q), jb = cand(min(q + 1, count - 1));
+        const double na = cn2[ja], nbn = cn2[jb];            // in flight together with the rows
+        double da, db;
+        wave_dot2<TR>(xr, C + size_t(ja) * nch, C + size_t(jb) * nch, nch, da, db);
+        take(ja, da, na);
+        if (jb != ja) take(jb, db, nbn);
+    }
+    bool kept = true;
+    if (nb.keep >= 0.0) {
+        double nx, unused;
+        wave_dot2<TR>(xr, xr, xr, nch, nx, unused);
+        kept = bd * bd >= nb.keep * nx * bc;
+    }
+    if ((threadIdx.x & 63) == 0) {
+        f[row] = bj;
+        alpha[row] = (kept && bc > 0.0) ? float(bd / bc) : 0.f;
+        if (!kept) atomicAdd(nb.dropped, 1);
     }
 }
 
@@ -307,7 +270,7 @@ __device__ __forceinline__ void drain_queue(const u32x4_t* __restrict__ X, const
 // alpha; otherwise it writes one candidate record per token and column block for k_finalize.
 template <typename TR, int TG, int TT, int NW, bool ALIGNED, bool FUSED>
 __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                                   const float* __restrict__ inv, const double* __restrict__ cn2,
+                                                   const float* __restrict__ rn, const double* __restrict__ cn2,
                                                    const unsigned long long* __restrict__ hash, int b, int nch, int k, int ncb,
                                                    u32x4_t* __restrict__ cand, int32_t* __restrict__ f, float* __restrict__ alpha,
                                                    double keep, int32_t* __restrict__ eta) {
@@ -329,9 +292,9 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     static_assert(GB * CPS % NT == 0, "stage does not divide over the threads");
 
     __shared__ u32x4_t lds_raw[2 * CBUF + NW * 2 * XSLOT];
-    __shared__ __attribute__((aligned(16))) float lds_inv[GB];
-    __shared__ int redo_count, drop_count;
-    __shared__ int redo_entries[FUSED ? 32 * TT * NW * kRedoInts : 1];   // every token of the tile could need a second look
+    __shared__ __attribute__((aligned(16))) float lds_rn[GB];               // 1/||C_j||, 0 for generators that cannot win
+    __shared__ unsigned long long lds_hash[FUSED ? GB : 1], lds_norm[FUSED ? GB : 1];
+    __shared__ int drop_count;
     u32x4_t* const lds_c = lds_raw;                                         // [2][CBUF]
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
@@ -348,10 +311,18 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     }
     const int gen0 = cb * GB;
 
-    if (tid == 0) { redo_count = 0; drop_count = 0; }          // published by the barriers of the main loop
-    for (int t = tid; t < GB; t += NT) {
-        const int j = gen0 + t;
-        lds_inv[t] = j < k ? inv[j] : -1.f;        // negative marks a slot past the last generator
+    if (tid == 0) drop_count = 0;                              // published by the barriers of the main loop
+    // The generators' factors 1/||C_j|| (0: cannot win); slots past the last generator count as generators that cannot
+    // win.  With one column block the workgroup finds the copies among its generators itself (below, while its first
+    // loads are in flight); with several, k_dedupe has done it.
+    constexpr int GPT = (GB + NT - 1) / NT;       // generators per thread
+    float rn_reg[GPT];
+    unsigned long long hash_reg[GPT], norm_reg[GPT];
+#pragma unroll
+    for (int q = 0; q < GPT; ++q) {
+        const int jj = min(gen0 + tid + NT * q, k - 1);
+        rn_reg[q] = rn[jj];
+        if (FUSED) { hash_reg[q] = hash[jj]; norm_reg[q] = (unsigned long long)__double_as_longlong(cn2[jj]); }
     }
 
     // coalesced view of this wave's tokens: load i of fragment tt covers rows 8i .. 8i+7, lane L the row 8i + L/8
@@ -380,7 +351,6 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         for (int i = 0; i < 4; ++i) nrm[t][i] = 0.f;
     }
 
-    const int nstages = (nch + CPS - 1) / CPS;
     const int nss = (nch + 7) / 8;               // super-steps
     // Every workgroup walks the hidden dimension from a different starting window and wraps around (a dot product
     // does not care where it starts).  Without this all workgroups sit at the same column of their rows at the same
@@ -453,6 +423,27 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     load_c(0, 0);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
+#pragma unroll
+    for (int q = 0; q < GPT; ++q) {
+        const int t = tid + NT * q;
+        if (t < GB) {
+            lds_rn[t] = gen0 + t < k ? rn_reg[q] : 0.f;
+            if (FUSED) { lds_hash[t] = hash_reg[q]; lds_norm[t] = norm_reg[q]; }
+        }
+    }
+    if (FUSED) {
+        // a generator whose row is a bit-identical copy of a lower-numbered one (same hash, same fp64 norm) can never
+        // win: lowest j takes a tie.  PARTS threads share the comparisons of one generator.
+        __syncthreads();
+        constexpr int PARTS = NT >= GB ? NT / GB : 1;
+        for (int e = tid; e < GB * PARTS; e += NT) {
+            const int t = e % GB, part = e / GB;
+            const unsigned long long h = lds_hash[t], c2 = lds_norm[t];
+            bool copy = false;
+            for (int q = part; q < t; q += PARTS) copy |= (lds_hash[q] == h) & (lds_norm[q] == c2);
+            if (copy) lds_rn[t] = 0.f;
+        }
+    }
     store_c(0, 0);
 #pragma unroll
     for (int d = 1; d <= PD; ++d) load_c(d, d % PD);        // stage d travels in register slot d % PD
@@ -534,103 +525,58 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         }
     }
 
-    // Epilogue.  D layout of the 32x32 MFMA: register i of lane (r,g) is generator 8*(i/4)+4*g+(i%4), token r.
-    // The scores go through LDS (all tiles are free after the last barrier) so that the scan over generators
-    // is a small rolled loop instead of hundreds of unrolled compare/select chains: each pass dumps PG
-    // generators x 32 tokens per wave, then lane (r,g) scans half of them for token r in increasing order.
-    constexpr int PFMAX = NW == 8 ? 2 : 4;
-    constexpr int PF = TG < PFMAX ? TG : PFMAX;   // fragments per pass
-    constexpr int PG = 32 * PF;              // generators per pass
-    constexpr int SROW = PG + 4;             // floats per token row (padding: conflict-free 16-byte accesses)
-    static_assert(NW * 32 * SROW * sizeof(float) <= sizeof(lds_raw), "score dump does not fit");
-    float* sdump = reinterpret_cast<float*>(lds_raw) + wave * (32 * SROW);
+    // Epilogue.  D layout of the 32x32 MFMA: register i of lane (r,g) is generator 8*(i/4)+4*g+(i%4) of its fragment,
+    // token r: the two lanes (r,0) and (r,1) hold the token's products with all generators of the block, and the scan
+    // runs on the accumulator registers themselves.  Per wave a little LDS (all tiles are free after the last barrier)
+    // takes the names of the generators that are too close to a token's best for fp32 to tell apart.
+    int* const tok_cnt = reinterpret_cast<int*>(lds_raw) + wave * (32 * (1 + kMaxNamed));
+    int* const tok_names = tok_cnt + 32;
+    static_assert(NW * 32 * (1 + kMaxNamed) * sizeof(int) <= sizeof(lds_raw), "candidate lists do not fit");
+    const Neighbourhood nb{keep, &drop_count};
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        auto dump = [&](int h) {                 // scores of pass h -> this wave's LDS tile, [token][generator]
+        // r(i,j) = |<X_i,C_j>| / ||C_j|| replaces the products (sign kept); largest and second largest of this lane's half
+        float m1 = -1.f, m2 = -1.f;
 #pragma unroll
-            for (int pf = 0; pf < PF; ++pf)
+        for (int a = 0; a < TG; ++a)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x16_t& v = acc[h * PF + pf][tt];
-                    *reinterpret_cast<float4*>(&sdump[r * SROW + 32 * pf + 8 * q + 4 * g]) =
-                        make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-                }
-            wave_lds_sync();
-        };
-        const float* srow = &sdump[r * SROW + g * (PG / 2)];
-
-        // Per lane, over its half of every pass: the largest score m1 (lowest j on ties) with its dot product, the
-        // lowest other generator reaching m1 exactly (jt), the largest score strictly below m1 (m2, lowest j: j2)
-        // and the largest strictly below m2 (m3, value only).
-        float m1 = -1.f, m2 = -2.f, m3 = -3.f, dm = 0.f;
-        int jm = 0, jt = -1, j2 = 0;
-#pragma unroll
-        for (int h = 0; h < TG / PF; ++h) {
-            dump(h);
-            const int jl0 = h * PG + g * (PG / 2);
-#pragma unroll 2
-            for (int c = 0; c < PG / 2; c += 4) {
-                const float4 d4 = *reinterpret_cast<const float4*>(&srow[c]);
-                const float4 iv4 = *reinterpret_cast<const float4*>(&lds_inv[jl0 + c]);
-                const float dd[4] = {d4.x, d4.y, d4.z, d4.w}, iv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+            for (int q = 0; q < 4; ++q) {
+                const float4 rn4 = *reinterpret_cast<const float4*>(&lds_rn[32 * a + 8 * q + 4 * g]);
+                const float rr[4] = {rn4.x, rn4.y, rn4.z, rn4.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float sc = iv[e] >= 0.f ? dd[e] * dd[e] * iv[e] : -3.f;      // slots past the last generator
-                    const int j = gen0 + jl0 + c + e;
-                    const bool up = sc > m1, tie = sc == m1;
-                    const bool mid = !up && !tie && sc > m2;
-                    const bool low = sc < m2 && sc > m3;
-                    m3 = (up || mid) ? m2 : (low ? sc : m3);
-                    j2 = up ? jm : (mid ? j : j2);
-                    m2 = up ? m1 : (mid ? sc : m2);
-                    jt = up ? -1 : ((tie && jt < 0) ? j : jt);
-                    dm = up ? dd[e] : dm;
-                    jm = up ? j : jm;
-                    m1 = up ? sc : m1;
+                    const float v = acc[a][tt][4 * q + e] * rr[e];
+                    acc[a][tt][4 * q + e] = v;
+                    const float x = fabsf(v);
+                    m2 = __builtin_amdgcn_fmed3f(m1, x, m2);          // m2 <= m1 always: the median is the new second largest
+                    m1 = fmaxf(m1, x);
                 }
             }
-            wave_lds_sync();
-        }
-        Best best;
-        best.init();
-        best.s1 = m1; best.j1 = jm; best.d1 = dm; best.jt = jt; best.s2 = m2; best.j2 = j2; best.s3 = m3;
-        // Second pass, in the rare wave where some lane has three distinct values within 2^-12 of each other: list who
-        // attains the values that close to the lane's maximum (only those can matter to the final decision).
-        const bool crowded = m1 > 0.f && m3 >= m1 * (1.f - 0x1p-12f);
-        if (__builtin_amdgcn_ballot_w64(crowded) != 0ull) {
-            const float thr = m1 * (1.f - 0x1p-12f);
-            best.s2 = -2.f; best.j2 = 0; best.s3 = -3.f; best.j3 = -1; best.s4 = -4.f;
-            if (!crowded) { best.s2 = m2; best.j2 = j2; best.s3 = m3; }
+        // who attains the largest: walking down, the lowest position (= lowest generator of this lane) stays
+        int p1 = 0;
+        float a1 = 0.f;
 #pragma unroll
-            for (int h = 0; h < TG / PF; ++h) {
-                dump(h);
-                const int jl0 = h * PG + g * (PG / 2);
-#pragma unroll 2
-                for (int c = 0; c < PG / 2; c += 4) {
-                    const float4 d4 = *reinterpret_cast<const float4*>(&srow[c]);
-                    const float4 iv4 = *reinterpret_cast<const float4*>(&lds_inv[jl0 + c]);
-                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w}, iv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+        for (int a = TG - 1; a >= 0; --a)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float sc = iv[e] >= 0.f ? dd[e] * dd[e] * iv[e] : -3.f;
-                        const bool hit = crowded && sc >= thr && sc < m1;
-                        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
-                            if (hit) best.insert_lower(sc, gen0 + jl0 + c + e);
-                        }
-                    }
-                }
-                wave_lds_sync();
+            for (int i = 15; i >= 0; --i) {
+                const float v = acc[a][tt][i];
+                const bool hit = fabsf(v) == m1;
+                p1 = hit ? a * 16 + i : p1;
+                a1 = hit ? v : a1;
             }
-        }
-        // the two lanes of a token join their halves
+        int j1 = gen0 + 32 * (p1 >> 4) + 8 * ((p1 & 15) >> 2) + 4 * g + (p1 & 3);
+        // the two lanes of a token join their halves (both end up with the same values)
         {
-            Best o;
-            o.s1 = __shfl_xor(best.s1, 32); o.j1 = __shfl_xor(best.j1, 32); o.d1 = __shfl_xor(best.d1, 32);
-            o.jt = __shfl_xor(best.jt, 32); o.s2 = __shfl_xor(best.s2, 32); o.j2 = __shfl_xor(best.j2, 32);
-            o.s3 = __shfl_xor(best.s3, 32); o.j3 = __shfl_xor(best.j3, 32); o.s4 = __shfl_xor(best.s4, 32);
-            best.merge(o);
+            const float om1 = __shfl_xor(m1, 32), om2 = __shfl_xor(m2, 32), oa1 = __shfl_xor(a1, 32);
+            const int oj1 = __shfl_xor(j1, 32);
+            const bool other = om1 > m1 || (om1 == m1 && oj1 < j1);
+            m2 = fmaxf(fminf(m1, om1), fmaxf(m2, om2));
+            m1 = other ? om1 : m1;
+            a1 = other ? oa1 : a1;
+            j1 = other ? oj1 : j1;
         }
         const int row = row_base + 32 * tt + r;
+        const bool valid = row < b;
         // ||X_i||^2: row 8 i + L/8 of the fragment was loaded by the eight lanes L/8 = const, as their load i
         float nx = 0.f;
         if (want_norm) {
@@ -642,68 +588,148 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 nx = (i == (r >> 3)) ? w : nx;
             }
         }
-        const Neighbourhood nb{keep, &drop_count};
-        if (FUSED) {
-            // (one column block: generator j's 1/||C_j||^2 sits in lds_inv[j], no need to go to memory for it)
-            decide_or_queue(lds_inv, cn2, hash, g == 0 && row < b, row, best, nx, nb, f, alpha, &redo_count, redo_entries);
-        } else {
-            if (g == 0 && row < b) {
-                u32x4_t* rec = cand + (size_t(row) * ncb + cb) * 2;
-                best.store(rec);
-                Best::store_norm(rec, nx);
+        // Too close to call in fp32: a second generator within the band.  Rare (about one token in a thousand), so the
+        // wave only then walks its registers again, to name everybody within the band of each such token's best.
+        const float thr = m1 * (1.f - kBand);
+        const bool tie = valid && m1 > 0.f && m2 >= thr;
+        int cnt = 0;
+        if (__builtin_amdgcn_ballot_w64(tie) != 0ull) {
+            if (lane < 32) tok_cnt[lane] = 0;
+            wave_lds_sync();
+            // one bit per register within the band (a limit no value reaches for the lanes without a tie), then the
+            // set bits one by one: short straight-line code, because all of it misses the instruction cache
+            const float lim = tie ? thr : __builtin_inff();
+#pragma unroll
+            for (int a0 = 0; a0 < TG; a0 += 2) {
+                uint32_t bits[2] = {0u, 0u};
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (a0 + h < TG) bits[h] |= (fabsf(acc[a0 + h][tt][i]) >= lim) ? (1u << i) : 0u;
+                uint32_t todo = bits[0] | (bits[1] << 16);
+                while (todo != 0u) {
+                    const int p = __ffs(int(todo)) - 1;              // fragment a0 + p / 16, register p % 16
+                    todo &= todo - 1u;
+                    const int slot = atomicAdd(&tok_cnt[r], 1);
+                    if (slot < kMaxNamed) tok_names[r * kMaxNamed + slot] = gen0 + 32 * (a0 + (p >> 4)) + 8 * ((p & 15) >> 2) + 4 * g + (p & 3);
+                }
             }
+            wave_lds_sync();
+            cnt = tie ? min(tok_cnt[r], kTooMany) : 0;
+        }
+        if (FUSED) {
+            bool drop, close_call;
+            nb.judge(m1, nx, drop, close_call);
+            const bool unsure = valid && (tie || close_call);
+            if (valid && !unsure && g == 0) {
+                f[row] = j1;
+                alpha[row] = drop ? 0.f : a1 * lds_rn[j1];              // one column block: gen0 = 0
+                if (drop) atomicAdd(&drop_count, 1);
+            }
+            // the wave's undecided tokens, one after the other, in fp64 by the whole wave
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(unsure && g == 0);
+            while (todo != 0ull) {
+                const int t = __ffsll((long long)todo) - 1;             // lane = token number within the fragment
+                todo &= todo - 1ull;
+                const int row_t = __shfl(row, t), j_t = __shfl(j1, t), cnt_t = __shfl(cnt, t);
+                second_look<TR>(X, C, cn2, nch, k, row_t, cnt_t > 0 ? tok_names + t * kMaxNamed : nullptr, cnt_t, cnt_t >= kTooMany,
+                                j_t, nb, f, alpha);
+            }
+        } else if (valid && g == 0) {
+            BlockRecord rec;
+            rec.m1 = m1; rec.a1 = a1; rec.j1 = j1; rec.cnt = cnt;
+#pragma unroll
+            for (int q = 0; q < kMaxNamed; ++q) rec.names[q] = (q < cnt) ? tok_names[r * kMaxNamed + q] : 0;
+            rec.store(cand + (size_t(row) * ncb + cb) * 2, nx);
         }
     }
-    if (FUSED) {
-        const Neighbourhood nb{keep, &drop_count};
+    if (FUSED && want_norm) {
         __syncthreads();
-        drain_queue<TR, NW>(X, C, cn2, nch, k, nb, f, alpha, &redo_count, redo_entries);
-        if (want_norm) {
-            __syncthreads();
-            if (tid == 0 && drop_count > 0) atomicAdd(eta, drop_count);
-        }
+        if (tid == 0 && drop_count > 0) atomicAdd(eta, drop_count);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_finalize: one thread per token; only needed when the generators span several column blocks.
+// k_finalize: only needed when the generators span several column blocks.  One thread per token joins the blocks'
+// records: the overall best, and every generator named within the band of it (a block's list holds all of its
+// generators within the band of the BLOCK's best, which reaches at least as far down).  A token with a single
+// candidate is decided on the spot; the others wait in LDS for the workgroup's waves, which re-decide them in fp64.
+constexpr int kMaxMerged = 8;                   // candidates of one token over all blocks; more: every generator again
+constexpr int kEntryInts = 3 + kMaxMerged;      // row, number of names (0: only the neighbourhood condition is in doubt; -1: all), j1, names
+
 template <typename TR>
 __global__ __launch_bounds__(256) void k_finalize(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
-                                                  const float* __restrict__ inv, const double* __restrict__ cn2,
-                                                  const unsigned long long* __restrict__ hash,
+                                                  const float* __restrict__ rn, const double* __restrict__ cn2,
                                                   const u32x4_t* __restrict__ cand, int b, int nch, int k, int ncb,
                                                   int32_t* __restrict__ f, float* __restrict__ alpha, double keep,
                                                   int32_t* __restrict__ eta) {
-    const int row = blockIdx.x * 256 + threadIdx.x;
-    const bool valid = row < b;
-    Best st;
-    st.init();
-    if (valid) {
-        for (int cb = 0; cb < ncb; ++cb) {
-            Best o;
-            o.load(cand + (size_t(row) * ncb + cb) * 2);
-            if (cb == 0) st = o; else st.merge(o);
-        }
-    }
-    __shared__ int redo_count, drop_count;
-    __shared__ int redo_entries[256 * kRedoInts];
-    if (threadIdx.x == 0) { redo_count = 0; drop_count = 0; }
+    __shared__ int q_count, drop_count;
+    __shared__ int q_list[256];
+    __shared__ int entries[256 * kEntryInts];           // one slot per thread; q_list names the slots in use
+    const int tid = threadIdx.x, row = blockIdx.x * 256 + tid;
+    if (tid == 0) { q_count = 0; drop_count = 0; }
     __syncthreads();
     const Neighbourhood nb{keep, &drop_count};
-    const float nx = (valid && keep >= 0.0) ? Best::load_norm(cand + size_t(row) * ncb * 2) : 0.f;    // every block stores the same value
-    decide_or_queue(inv, cn2, hash, valid, row, st, nx, nb, f, alpha, &redo_count, redo_entries);
+    if (row < b) {
+        const u32x4_t* recs = cand + size_t(row) * ncb * 2;
+        float m1 = -1.f, a1 = 0.f;
+        int j1 = 0;
+        for (int cb = 0; cb < ncb; ++cb) {
+            BlockRecord rec;
+            rec.load_lead(recs + 2 * cb);
+            if (rec.m1 > m1 || (rec.m1 == m1 && rec.j1 < j1)) { m1 = rec.m1; a1 = rec.a1; j1 = rec.j1; }
+        }
+        int* e = entries + tid * kEntryInts;
+        int n = 0;
+        bool many = false;
+        auto add = [&](int j) {
+            if (n < kMaxMerged) e[3 + n++] = j; else many = true;
+        };
+        if (m1 > 0.f) {
+            const float thr = m1 * (1.f - kBand);
+            for (int cb = 0; cb < ncb; ++cb) {
+                BlockRecord rec;
+                rec.load_lead(recs + 2 * cb);
+                if (rec.m1 < thr) continue;
+                if (rec.cnt == 0) { add(rec.j1); continue; }
+                if (rec.cnt > kMaxNamed) { many = true; continue; }
+                rec.load_rest(recs + 2 * cb);
+#pragma unroll
+                for (int q = 0; q < kMaxNamed; ++q)
+                    if (q < rec.cnt) add(rec.names[q]);
+            }
+        }
+        const bool tie = many || n > 1;
+        const float nx = keep >= 0.0 ? BlockRecord::load_norm(recs) : 0.f;      // every block stores the same value
+        bool drop, close_call;
+        nb.judge(m1, nx, drop, close_call);
+        if (!tie && !close_call) {
+            f[row] = j1;
+            alpha[row] = drop ? 0.f : a1 * rn[j1];
+            if (drop) atomicAdd(&drop_count, 1);
+        } else {
+            e[0] = row; e[1] = tie ? (many ? -1 : n) : 0; e[2] = j1;
+            q_list[atomicAdd(&q_count, 1)] = tid;
+        }
+    }
     __syncthreads();
-    drain_queue<TR, 4>(X, C, cn2, nch, k, nb, f, alpha, &redo_count, redo_entries);
+    const int total = q_count;
+    for (int t = tid >> 6; t < total; t += 4) {
+        const int* e = entries + q_list[t] * kEntryInts;
+        const int n = e[1];
+        second_look<TR>(X, C, cn2, nch, k, e[0], n != 0 ? e + 3 : nullptr, n, n < 0, e[2], nb, f, alpha);
+    }
     if (keep >= 0.0) {
         __syncthreads();
-        if (threadIdx.x == 0 && drop_count > 0) atomicAdd(eta, drop_count);
+        if (tid == 0 && drop_count > 0) atomicAdd(eta, drop_count);
     }
 }
 
 // ------------------------------------------------------------------------------------------------ host side
 
 struct ScoreArgs {
-    const void* X; const void* C; const float* inv; const double* cn2; const unsigned long long* hash;
+    const void* X; const void* C; const float* rn; const double* cn2; const unsigned long long* hash;
     int b, nch, k;
     u32x4_t* cand; int32_t* f; float* alpha;
     double keep; int32_t* eta;
@@ -714,10 +740,10 @@ static void launch_score_cfg(const CompressPlan& pl, const ScoreArgs& a, hipStre
     dim3 grid((unsigned)(pl.ncb > 1 ? (pl.row_tiles + 7) / 8 * 8 * pl.ncb : pl.row_tiles));
     if (a.nch % 8 == 0)      // every row is a whole number of 128-byte super-steps
         hipLaunchKernelGGL((k_score<TR, TG, TT, NW, true, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
-                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
+                           (const u32x4_t*)a.C, a.rn, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
     else
         hipLaunchKernelGGL((k_score<TR, TG, TT, NW, false, FUSED>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)a.X,
-                           (const u32x4_t*)a.C, a.inv, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
+                           (const u32x4_t*)a.C, a.rn, a.cn2, a.hash, a.b, a.nch, a.k, pl.ncb, a.cand, a.f, a.alpha, a.keep, a.eta);
 }
 
 template <typename TR, int TG, bool FUSED>
@@ -752,7 +778,7 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
                                 hipStream_t s) {
     const int nch = n / TR::kPerChunk;
     int32_t* idx = reinterpret_cast<int32_t*>(ws + pl.off_idx);
-    float* inv = reinterpret_cast<float*>(ws + pl.off_inv);
+    float* rn = reinterpret_cast<float*>(ws + pl.off_rn);
     double* cn2 = reinterpret_cast<double*>(ws + pl.off_cn2);
     unsigned long long* hash = reinterpret_cast<unsigned long long*>(ws + pl.off_hash);
     u32x4_t* cand = reinterpret_cast<u32x4_t*>(ws + pl.off_cand);
@@ -760,7 +786,7 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
     {
         ScopedSpan span(kGather, s);
         if (idx_dev) {
-            hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_dev, b, nch, (u32x4_t*)C, idx, inv, cn2,
+            hipLaunchKernelGGL((k_gather<TR>), dim3(k), dim3(256), 0, s, (const u32x4_t*)X, idx_dev, b, nch, (u32x4_t*)C, idx, rn, cn2,
                                hash, eta);
         } else {
             for (int j0 = 0; j0 < k; j0 += kArgGenerators) {
@@ -768,18 +794,20 @@ static pamm_status run_compress(const CompressPlan& pl, const void* X, int b, in
                 IdxByValue ia;
                 for (int j = 0; j < kArgGenerators; ++j) ia.v[j] = j < cnt ? idx_host[j0 + j] : 0;
                 hipLaunchKernelGGL((k_gather_arg<TR>), dim3(cnt), dim3(256), 0, s, (const u32x4_t*)X, ia, j0, b, nch, (u32x4_t*)C, idx,
-                                   inv, cn2, hash, eta);
+                                   rn, cn2, hash, eta);
             }
         }
+        if (pl.ncb > 1)
+            hipLaunchKernelGGL(k_dedupe, dim3((k + 63) / 64), dim3(256), 0, s, cn2, hash, k, rn);
     }
     {
         ScopedSpan span(kScore, s);
-        launch_score<TR>(pl, ScoreArgs{X, C, inv, cn2, hash, b, nch, k, cand, f, alpha, keep, eta}, s);
+        launch_score<TR>(pl, ScoreArgs{X, C, rn, cn2, hash, b, nch, k, cand, f, alpha, keep, eta}, s);
     }
     if (pl.ncb > 1) {
         ScopedSpan span(kFinalize, s);
-        hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, inv, cn2,
-                           hash, cand, b, nch, k, pl.ncb, f, alpha, keep, eta);
+        hipLaunchKernelGGL((k_finalize<TR>), dim3((b + 255) / 256), dim3(256), 0, s, (const u32x4_t*)X, (const u32x4_t*)C, rn, cn2,
+                           cand, b, nch, k, pl.ncb, f, alpha, keep, eta);
     }
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }

@@ -37,7 +37,7 @@ struct CompressPlan {
     int ncb;         // column blocks = ceil(k / (32*tg))
     int64_t row_tiles;
     // workspace offsets (bytes)
-    size_t off_idx, off_inv, off_cn2, off_hash, off_cand, total;
+    size_t off_idx, off_rn, off_cn2, off_hash, off_cand, total;
 };
 
 inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt, CompressPlan* p) {
@@ -74,7 +74,7 @@ inline pamm_status plan_compress(int64_t b, int64_t n, int64_t k, pamm_dtype dt,
     p->row_tiles = (b + tile_tokens - 1) / tile_tokens;
     size_t o = 0;
     p->off_idx = o;  o = align_up(o + size_t(k) * 4, 256);
-    p->off_inv = o;  o = align_up(o + size_t(k) * 4, 256);
+    p->off_rn = o;   o = align_up(o + size_t(k) * 4, 256);
     p->off_cn2 = o;  o = align_up(o + size_t(k) * 8, 256);
     p->off_hash = o; o = align_up(o + size_t(k) * 8, 256);
     p->off_cand = o; o = align_up(o + size_t(b) * size_t(p->ncb) * 32, 256);
