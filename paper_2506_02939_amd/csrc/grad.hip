@@ -17,6 +17,7 @@
 #include "pamm_device.h"
 #include "pamm_plan.h"
 #include "pamm_profile.h"
+#include "pamm_tile256.h"
 
 namespace pamm {
 
@@ -915,6 +916,75 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
     }
 }
 
+// k_ctb_big: the same product for the shapes where the matrix cores are the limit (many generators, large weight
+// gradient; bf16 operands): 256 x 256 tiles on the shared main loop of pamm_tile256.h.  The operands' rows hold a whole
+// number of 128-generator groups (k_prep pads with zero generators).  Tile order, store layout and the bf16 packing are
+// those of k_ctb, over 4 x 4 accumulator fragments per wave.
+template <bool OUT16>
+__global__ __launch_bounds__(256) void k_ctb_big(const u32x4_t* __restrict__ Ct, const u32x4_t* __restrict__ Bt, int n, int m, int KC,
+                                                 int tiles_n, int tiles_m, int per_xcd, void* __restrict__ dWv) {
+    __shared__ u32x4_t lds[kTileBuffers * kTileStageChunks];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
+    const int wy = wave >> 1, wx = wave & 1;
+    const int L = int(blockIdx.x % 8) * per_xcd + int(blockIdx.x / 8);
+    if (L >= tiles_n * tiles_m) return;          // uniform for the workgroup
+    int tl, tc;
+    {
+        const int full = tiles_m / 8, rem = tiles_m % 8, per_strip = tiles_n * 8;
+        if (L < full * per_strip) { const int q = L % per_strip; tl = q / 8; tc = (L / per_strip) * 8 + q % 8; }
+        else { const int q = L - full * per_strip; tl = q / rem; tc = full * 8 + q % rem; }
+    }
+    const int l0 = tl * 256, c0 = tc * 256;
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][q][i] = 0.f;
+    const TileSource src = tile_source(Ct, l0, n, size_t(KC), Bt, c0, m, size_t(KC));
+    tile_mainloop(lds, src, KC / 4, acc);
+
+    const int lw = l0 + wy * 128, cw = c0 + wx * 128;
+    const bool inside = l0 + 256 <= n && c0 + 256 <= m;      // uniform: a tile away from the edges stores unguarded
+    if constexpr (!OUT16) {
+        float* __restrict__ dW = static_cast<float*>(dWv);
+#pragma unroll
+        for (int fa = 0; fa < 4; ++fa)
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) {
+                const int c = cw + 32 * fb + r;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int l = lw + 32 * fa + 8 * (i >> 2) + 4 * g + (i & 3);
+                    if (inside || (l < n && c < m)) __builtin_nontemporal_store(acc[fa][fb][i], &dW[size_t(l) * m + c]);
+                }
+            }
+    } else {
+        uint32_t* __restrict__ dW = static_cast<uint32_t*>(dWv);
+        const bool odd = r & 1;
+#pragma unroll
+        for (int fa = 0; fa < 4; ++fa)
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) {
+                const int c = cw + 32 * fb + (r & ~1);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float v0 = acc[fa][fb][4 * q], v1 = acc[fa][fb][4 * q + 1], v2 = acc[fa][fb][4 * q + 2],
+                                v3 = acc[fa][fb][4 * q + 3];
+                    const float got0 = __shfl_xor(odd ? v0 : v2, 1), got1 = __shfl_xor(odd ? v1 : v3, 1);
+                    const uint32_t p0 = odd ? pack_bf16(got0, v2) : pack_bf16(v0, got0);
+                    const uint32_t p1 = odd ? pack_bf16(got1, v3) : pack_bf16(v1, got1);
+                    const int l = lw + 32 * fa + 8 * q + 4 * g + (odd ? 2 : 0);
+                    if (c < m) {
+                        if (l < n) __builtin_nontemporal_store(p0, &dW[(size_t(l) * m + c) >> 1]);
+                        if (l + 1 < n) __builtin_nontemporal_store(p1, &dW[(size_t(l + 1) * m + c) >> 1]);
+                    }
+                }
+            }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ host side
 
 struct GradBuffers {
@@ -1002,6 +1072,19 @@ static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void
     const u32x4_t* rows_op = m_by_n ? g.bt : g.ct;
     const u32x4_t* cols_op = m_by_n ? g.ct : g.bt;
     const int nr = m_by_n ? m : n, nc = m_by_n ? n : m;
+    if (pl.big_tiles) {
+        if constexpr (std::is_same<TR, Bf16>::value) {
+            const int tiles_r = (nr + 255) / 256, tiles_c = (nc + 255) / 256;
+            const int per_xcd = (tiles_r * tiles_c + 7) / 8;
+            ScopedSpan span(kCtb, s);
+            const dim3 grid((unsigned)(per_xcd * 8));
+            if (out16)
+                hipLaunchKernelGGL((k_ctb_big<true>), grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, KC, tiles_r, tiles_c, per_xcd, dW);
+            else
+                hipLaunchKernelGGL((k_ctb_big<false>), grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, KC, tiles_r, tiles_c, per_xcd, dW);
+        }
+        return;
+    }
     const int tiles_r = (nr + 127) / 128, tiles_c = (nc + 127) / 128;
     const int per_xcd = (tiles_r * tiles_c + 7) / 8;
     {

@@ -201,3 +201,31 @@ def test_near_ties_on_rows_far_from_every_generator(pamm, oracle, dn, n, cos):
     wrong = int(np.sum(f[sure] != ora.f[sure]))
     print(f"[near-tie] {dn} n={n} cos={cos}: {close} rows between 1e-6 and 2^-12, {wrong} decided differently", flush=True)
     assert wrong == 0
+
+
+# ------------------------------------------------------------------------------------------ the 256 x 256 tiles of C^T Btilde
+
+@pytest.mark.parametrize("form", ["f32", "bf16", "f32_m_by_n", "bf16_m_by_n"])
+def test_big_tiles_of_the_small_product(pamm, oracle, form):
+    """At least 512 generators and at least 512 tiles of 256 x 256: the product C^T Btilde takes the kernel built on the
+    shared 256 x 256 main loop.  Ragged edges in both directions, 520 generators (padded to 640 with zero generators), all
+    four output forms, against the oracle element by element."""
+    w = workloads.scaled(workloads.WORKLOADS["llama7b_k1024"], name="big_tiles", seqs=2, seq_len=1024, n=4000, m=8200, k=520, centres=300)
+    X, dY = workloads.generate(w)
+    got = pamm.compress(X.cuda(), w.k, seed=3)
+    torch.cuda.synchronize()
+    f = got.f.cpu().numpy()
+    a = got.alpha.cpu().numpy().astype(np.float64)
+    C64 = oracle.to_f64(got.C.cpu())
+    _, O = oracle.grad(C64, f, a, dY)
+    _, O_abs = oracle.grad(np.abs(C64), f, np.abs(a), dY.abs())
+    kw = dict(out_dtype=torch.bfloat16 if form.startswith("bf16") else torch.float32, transposed=form.endswith("m_by_n"))
+    dW = pamm.grad(got.C, got.f, got.alpha, dY.cuda(), **kw)
+    torch.cuda.synchronize()
+    res = dW.float().cpu().numpy().astype(np.float64)
+    if kw["transposed"]:
+        res = res.T
+    bar = ELEM_DW["bf16"] + (2.0 ** -8 if form.startswith("bf16") else 0.0)        # + one rounding of the result itself
+    err = np.abs(res - O)
+    assert np.all(err <= bar * O_abs + 1e-30), f"dW off by {np.max(err / np.maximum(O_abs, 1e-300))}"
+    assert np.linalg.norm(err) <= (2.0 ** -8 + (2.0 ** -9 if form.startswith("bf16") else 0.0)) * np.linalg.norm(O)
