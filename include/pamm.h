@@ -228,6 +228,7 @@ const char *pamm_kernel_name(int id);
  *   piece_rows     positions of the sorted list per chunk of the contraction: a multiple of 16 in [16, 4096]
  *   contract_w     512-column groups per wave of the contraction: 1, 2 or 3
  *   sort_one_rows  largest b grouped by the single-workgroup counting sort: 1..16384
+ *   small_tiles    1: the 256 x 256 tile kernel that C^T Btilde takes at large shapes with at least 512 generators is not used
  *
  * pamm_debug_bounded writes `count` consecutive draws of the sampler's bounded step (uniform on [0, range) by
  * rejection, as specified at pamm_sample_indices) from one generator seeded with `seed` into out_host, so that a
@@ -235,7 +236,7 @@ const char *pamm_kernel_name(int id);
  * probability below 2^-33.  range = 0 or out_host = NULL: PAMM_ERR_INVALID_ARG.
  */
 typedef struct {
-    int score_tg, score_nw, piece_rows, contract_w, sort_one_rows;
+    int score_tg, score_nw, piece_rows, contract_w, sort_one_rows, small_tiles;
 } pamm_debug_plan;
 pamm_status pamm_debug_set_plan(const pamm_debug_plan *plan_host);
 pamm_status pamm_debug_bounded(uint64_t seed, uint64_t range, int64_t count, uint64_t *out_host);

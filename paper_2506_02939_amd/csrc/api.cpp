@@ -8,7 +8,7 @@ using namespace pamm;
 
 namespace pamm {
 Profiler g_profiler;
-pamm_debug_plan g_plan_override = {0, 0, 0, 0, 0};
+pamm_debug_plan g_plan_override = {0, 0, 0, 0, 0, 0};
 }
 
 extern "C" const char* pamm_status_string(pamm_status s) {
@@ -76,7 +76,7 @@ extern "C" pamm_status pamm_sample_indices(int64_t b, int64_t k, uint64_t seed, 
 }
 
 extern "C" pamm_status pamm_debug_set_plan(const pamm_debug_plan* plan_host) {
-    g_plan_override = plan_host ? *plan_host : pamm_debug_plan{0, 0, 0, 0, 0};
+    g_plan_override = plan_host ? *plan_host : pamm_debug_plan{0, 0, 0, 0, 0, 0};
     return PAMM_OK;
 }
 

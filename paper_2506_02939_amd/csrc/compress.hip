@@ -250,6 +250,79 @@ __device__ __noinline__ void second_look(const u32x4_t* __restrict__ X, const u3
 }
 
 // ------------------------------------------------------------------------------------------------
+// The scan of one token fragment on the accumulator registers.  D layout of the 32x32 MFMA: register i of lane (r,g)
+// in generator fragment a is generator 32 a + 8 (i/4) + 4 g + (i%4) of the lane's generators, token r: the two lanes
+// (r,0) and (r,1) hold the token's products with all of them.
+__device__ __forceinline__ int lane_generator(int p, int g) { return 32 * (p >> 4) + 8 * ((p & 15) >> 2) + 4 * g + (p & 3); }
+
+// r(i,j) = <X_i,C_j> / ||C_j|| replaces the products (sign kept; rn: the factors of this wave's generators in LDS);
+// returns the largest and second largest |r| over the two lanes' generators, the lowest generator (numbered from
+// jbase) attaining the largest, and the signed value there.  Both lanes of a token end up with the same values.
+template <int NA, int NQ>
+__device__ __forceinline__ void scan_fragment(f32x16_t (&acc)[NA][NQ], int tq, const float* rn, int g, int jbase, float& m1, float& m2,
+                                              int& j1, float& a1) {
+    m1 = -1.f; m2 = -1.f;
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 rn4 = *reinterpret_cast<const float4*>(&rn[32 * a + 8 * q + 4 * g]);
+            const float rr[4] = {rn4.x, rn4.y, rn4.z, rn4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = acc[a][tq][4 * q + e] * rr[e];
+                acc[a][tq][4 * q + e] = v;
+                const float x = fabsf(v);
+                m2 = __builtin_amdgcn_fmed3f(m1, x, m2);          // m2 <= m1 always: the median is the new second largest
+                m1 = fmaxf(m1, x);
+            }
+        }
+    // who attains the largest: walking down, the lowest position (= lowest generator of this lane) stays
+    int p1 = 0;
+    a1 = 0.f;
+#pragma unroll
+    for (int a = NA - 1; a >= 0; --a)
+#pragma unroll
+        for (int i = 15; i >= 0; --i) {
+            const float v = acc[a][tq][i];
+            const bool hit = fabsf(v) == m1;
+            p1 = hit ? a * 16 + i : p1;
+            a1 = hit ? v : a1;
+        }
+    j1 = jbase + lane_generator(p1, g);
+    const float om1 = __shfl_xor(m1, 32), om2 = __shfl_xor(m2, 32), oa1 = __shfl_xor(a1, 32);
+    const int oj1 = __shfl_xor(j1, 32);
+    const bool other = om1 > m1 || (om1 == m1 && oj1 < j1);
+    m2 = fmaxf(fminf(m1, om1), fmaxf(m2, om2));
+    m1 = other ? om1 : m1;
+    a1 = other ? oa1 : a1;
+    j1 = other ? oj1 : j1;
+}
+
+// Names every generator of this lane whose |r| reaches lim (+infinity for lanes that have nothing to name) into the
+// token's list in LDS: cnt[0] counts, names[0..kMaxNamed) takes the first ones.  One bit per register, then the set
+// bits one by one: short straight-line code, because all of it misses the instruction cache.
+template <int NA, int NQ>
+__device__ __forceinline__ void name_fragment(const f32x16_t (&acc)[NA][NQ], int tq, float lim, int g, int jbase, int* cnt, int* names) {
+#pragma unroll
+    for (int a0 = 0; a0 < NA; a0 += 2) {
+        uint32_t bits[2] = {0u, 0u};
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (a0 + h < NA) bits[h] |= (fabsf(acc[a0 + h][tq][i]) >= lim) ? (1u << i) : 0u;
+        uint32_t todo = bits[0] | (bits[1] << 16);
+        while (todo != 0u) {
+            const int p = __ffs(int(todo)) - 1;              // fragment a0 + p / 16, register p % 16
+            todo &= todo - 1u;
+            const int slot = atomicAdd(cnt, 1);
+            if (slot < kMaxNamed) names[slot] = jbase + lane_generator(16 * a0 + p, g);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // k_score.  Workgroup = NW waves; wave w owns 32*TT tokens; the workgroup owns one column block of
 // 32*TG generators.  Roles in the 32x32 MFMA: A operand = generators, B operand = tokens, so a lane
 // ends up holding scores of ONE token (lane%32) against 16*TG generators per token fragment.
@@ -525,56 +598,18 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         }
     }
 
-    // Epilogue.  D layout of the 32x32 MFMA: register i of lane (r,g) is generator 8*(i/4)+4*g+(i%4) of its fragment,
-    // token r: the two lanes (r,0) and (r,1) hold the token's products with all generators of the block, and the scan
-    // runs on the accumulator registers themselves.  Per wave a little LDS (all tiles are free after the last barrier)
-    // takes the names of the generators that are too close to a token's best for fp32 to tell apart.
+    // Epilogue: the scan runs on the accumulator registers themselves (scan_fragment).  Per wave a little LDS (all tiles
+    // are free after the last barrier) takes the names of the generators that are too close to a token's best for fp32
+    // to tell apart.
     int* const tok_cnt = reinterpret_cast<int*>(lds_raw) + wave * (32 * (1 + kMaxNamed));
     int* const tok_names = tok_cnt + 32;
     static_assert(NW * 32 * (1 + kMaxNamed) * sizeof(int) <= sizeof(lds_raw), "candidate lists do not fit");
     const Neighbourhood nb{keep, &drop_count};
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        // r(i,j) = |<X_i,C_j>| / ||C_j|| replaces the products (sign kept); largest and second largest of this lane's half
-        float m1 = -1.f, m2 = -1.f;
-#pragma unroll
-        for (int a = 0; a < TG; ++a)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 rn4 = *reinterpret_cast<const float4*>(&lds_rn[32 * a + 8 * q + 4 * g]);
-                const float rr[4] = {rn4.x, rn4.y, rn4.z, rn4.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float v = acc[a][tt][4 * q + e] * rr[e];
-                    acc[a][tt][4 * q + e] = v;
-                    const float x = fabsf(v);
-                    m2 = __builtin_amdgcn_fmed3f(m1, x, m2);          // m2 <= m1 always: the median is the new second largest
-                    m1 = fmaxf(m1, x);
-                }
-            }
-        // who attains the largest: walking down, the lowest position (= lowest generator of this lane) stays
-        int p1 = 0;
-        float a1 = 0.f;
-#pragma unroll
-        for (int a = TG - 1; a >= 0; --a)
-#pragma unroll
-            for (int i = 15; i >= 0; --i) {
-                const float v = acc[a][tt][i];
-                const bool hit = fabsf(v) == m1;
-                p1 = hit ? a * 16 + i : p1;
-                a1 = hit ? v : a1;
-            }
-        int j1 = gen0 + 32 * (p1 >> 4) + 8 * ((p1 & 15) >> 2) + 4 * g + (p1 & 3);
-        // the two lanes of a token join their halves (both end up with the same values)
-        {
-            const float om1 = __shfl_xor(m1, 32), om2 = __shfl_xor(m2, 32), oa1 = __shfl_xor(a1, 32);
-            const int oj1 = __shfl_xor(j1, 32);
-            const bool other = om1 > m1 || (om1 == m1 && oj1 < j1);
-            m2 = fmaxf(fminf(m1, om1), fmaxf(m2, om2));
-            m1 = other ? om1 : m1;
-            a1 = other ? oa1 : a1;
-            j1 = other ? oj1 : j1;
-        }
+        float m1, m2, a1;
+        int j1;
+        scan_fragment(acc, tt, lds_rn, g, gen0, m1, m2, j1, a1);
         const int row = row_base + 32 * tt + r;
         const bool valid = row < b;
         // ||X_i||^2: row 8 i + L/8 of the fragment was loaded by the eight lanes L/8 = const, as their load i
@@ -596,25 +631,7 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
         if (__builtin_amdgcn_ballot_w64(tie) != 0ull) {
             if (lane < 32) tok_cnt[lane] = 0;
             wave_lds_sync();
-            // one bit per register within the band (a limit no value reaches for the lanes without a tie), then the
-            // set bits one by one: short straight-line code, because all of it misses the instruction cache
-            const float lim = tie ? thr : __builtin_inff();
-#pragma unroll
-            for (int a0 = 0; a0 < TG; a0 += 2) {
-                uint32_t bits[2] = {0u, 0u};
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (a0 + h < TG) bits[h] |= (fabsf(acc[a0 + h][tt][i]) >= lim) ? (1u << i) : 0u;
-                uint32_t todo = bits[0] | (bits[1] << 16);
-                while (todo != 0u) {
-                    const int p = __ffs(int(todo)) - 1;              // fragment a0 + p / 16, register p % 16
-                    todo &= todo - 1u;
-                    const int slot = atomicAdd(&tok_cnt[r], 1);
-                    if (slot < kMaxNamed) tok_names[r * kMaxNamed + slot] = gen0 + 32 * (a0 + (p >> 4)) + 8 * ((p & 15) >> 2) + 4 * g + (p & 3);
-                }
-            }
+            name_fragment(acc, tt, tie ? thr : __builtin_inff(), g, gen0, &tok_cnt[r], &tok_names[r * kMaxNamed]);
             wave_lds_sync();
             cnt = tie ? min(tok_cnt[r], kTooMany) : 0;
         }

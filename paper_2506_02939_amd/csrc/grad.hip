@@ -918,12 +918,12 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
 
 // k_ctb_big: the same product for the shapes where the matrix cores are the limit (many generators, large weight
 // gradient; bf16 operands): 256 x 256 tiles on the shared main loop of pamm_tile256.h.  The operands' rows hold a whole
-// number of 128-generator groups (k_prep pads with zero generators).  Tile order, store layout and the bf16 packing are
+// number of 32-generator stages (k_prep pads with zero generators).  Tile order, store layout and the bf16 packing are
 // those of k_ctb, over 4 x 4 accumulator fragments per wave.
 template <bool OUT16>
 __global__ __launch_bounds__(256) void k_ctb_big(const u32x4_t* __restrict__ Ct, const u32x4_t* __restrict__ Bt, int n, int m, int KC,
                                                  int tiles_n, int tiles_m, int per_xcd, void* __restrict__ dWv) {
-    __shared__ u32x4_t lds[kTileBuffers * kTileStageChunks];
+    __shared__ u32x4_t lds[TileLds<4, 4>::kChunks];        // both operands come from L2 / Infinity Cache: equal rings
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
     const int wy = wave >> 1, wx = wave & 1;
     const int L = int(blockIdx.x % 8) * per_xcd + int(blockIdx.x / 8);
@@ -943,7 +943,7 @@ __global__ __launch_bounds__(256) void k_ctb_big(const u32x4_t* __restrict__ Ct,
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][q][i] = 0.f;
     const TileSource src = tile_source(Ct, l0, n, size_t(KC), Bt, c0, m, size_t(KC));
-    tile_mainloop(lds, src, KC / 4, acc);
+    tile_mainloop<4, 4>(lds, src, KC / 4, 0, acc);
 
     const int lw = l0 + wy * 128, cw = c0 + wx * 128;
     const bool inside = l0 + 256 <= n && c0 + 256 <= m;      // uniform: a tile away from the edges stores unguarded

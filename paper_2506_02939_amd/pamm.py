@@ -246,7 +246,7 @@ def contract(f: torch.Tensor, alpha: torch.Tensor, dY: torch.Tensor, k: int, *, 
 
 
 class _DebugPlan(ctypes.Structure):
-    _fields_ = [(name, ctypes.c_int) for name in ("score_tg", "score_nw", "piece_rows", "contract_w", "sort_one_rows")]
+    _fields_ = [(name, ctypes.c_int) for name in ("score_tg", "score_nw", "piece_rows", "contract_w", "sort_one_rows", "small_tiles")]
 
 
 def debug_set_plan(**overrides: int) -> None:

@@ -45,7 +45,7 @@ int main() {
 
     // ---- planners and workspace queries over ordinary and extreme sizes, with and without overrides
     const int64_t big = (int64_t(1) << 31) - 8;
-    const pamm_debug_plan plans[] = {{0, 0, 0, 0, 0}, {1, 2, 16, 1, 1}, {8, 8, 4096, 3, 16384}, {3, 5, 17, 9, -4}};
+    const pamm_debug_plan plans[] = {{0, 0, 0, 0, 0, 0}, {1, 2, 16, 1, 1, 0}, {8, 8, 4096, 3, 16384, 1}, {3, 5, 17, 9, -4, 0}, {0, 0, 0, 0, 0, 1}};
     for (const pamm_debug_plan& pp : plans) {
         REQUIRE(pamm_debug_set_plan(&pp) == PAMM_OK);
         for (pamm_dtype dt : {PAMM_F32, PAMM_BF16})

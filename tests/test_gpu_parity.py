@@ -171,6 +171,10 @@ SMALL = [
     # the largest k the library takes, with every row a generator (k = b): 64 column blocks in k_score, one grouping
     # workgroup per generator, the pinned index ring; the padding rows of the recipe are bit-identical generators
     ("bf16_k16384_every_row_a_generator", "llama60m", dict(seqs=4, seq_len=4096, n=16, m=24, k=16384, centres=64)),
+    # many generators, four and three column blocks, the last one partly filled; 10 % padding rows, so many generators
+    # are bit-identical copies of a lower-numbered one
+    ("bf16_k1000_four_column_blocks", "llama60m", dict(seqs=10, seq_len=830, n=256, m=264, k=1000, centres=700)),
+    ("bf16_k520_three_column_blocks_long_rows", "llama1b", dict(seqs=1, seq_len=16500, n=1152, m=72, k=520, centres=4000)),
 ]
 
 

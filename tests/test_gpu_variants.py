@@ -229,3 +229,4 @@ def test_big_tiles_of_the_small_product(pamm, oracle, form):
     err = np.abs(res - O)
     assert np.all(err <= bar * O_abs + 1e-30), f"dW off by {np.max(err / np.maximum(O_abs, 1e-300))}"
     assert np.linalg.norm(err) <= (2.0 ** -8 + (2.0 ** -9 if form.startswith("bf16") else 0.0)) * np.linalg.norm(O)
+
