@@ -230,3 +230,31 @@ def test_big_tiles_of_the_small_product(pamm, oracle, form):
     assert np.all(err <= bar * O_abs + 1e-30), f"dW off by {np.max(err / np.maximum(O_abs, 1e-300))}"
     assert np.linalg.norm(err) <= (2.0 ** -8 + (2.0 ** -9 if form.startswith("bf16") else 0.0)) * np.linalg.norm(O)
 
+
+# ------------------------------------------------------------------------------------------ nearly identical rows
+
+def test_nearly_identical_rows_stay_correct_and_affordable(pamm, oracle):
+    """The method's own regime taken to the extreme: every row is one centre plus noise of relative size 1e-4, no two
+    rows bit-identical.  All generators are then nearly parallel, every token has every generator within the fp32 band
+    of its best, and each token is decided in fp64 among all of them.  f must still be the oracle's wherever the oracle's
+    two best scores are 1e-6 apart, alpha within the bar, and the call must stay within a small multiple of a second."""
+    import time
+
+    g = torch.Generator().manual_seed(23)
+    b, n, k = 4096, 512, 24
+    centre = torch.randn(n, generator=g)
+    X = (centre[None, :] * (1.0 + 0.5 * torch.rand(b, 1, generator=g)) + 1e-4 * centre.norm() / n ** 0.5 * torch.randn(b, n, generator=g))
+    for dt in (torch.float32, torch.bfloat16):
+        Xc = X.to(dt)
+        ora = oracle.compress(Xc, k, seed=2)
+        Xg = Xc.cuda()
+        pamm.compress(Xg, k, seed=2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        got = pamm.compress(Xg, k, seed=2)
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        _check_compress(ora, got, None)
+        crowded = float(np.mean(_gap(ora) < 2.0 ** -12))
+        print(f"[near-duplicates] {dt}: {crowded:.2f} of the rows within the fp32 band, compress took {dt_s * 1e3:.2f} ms", flush=True)
+        assert dt_s < 0.5
