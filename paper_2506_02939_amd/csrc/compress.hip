@@ -127,23 +127,32 @@ __global__ __launch_bounds__(256) void k_gather_arg(const u32x4_t* __restrict__ 
 // k_dedupe: for the shapes with several column blocks (with one block the score kernel does this itself), rn[j] <- 0
 // for every generator whose row is a bit-identical copy of a lower-numbered one (same content hash, same fp64 norm):
 // it can never win, lowest j takes a tie.  64 generators per workgroup, four threads each, which share the
-// comparisons with the lower-numbered generators; their (hash, norm) pairs pass through LDS in tiles of 256.
+// comparisons with the lower-numbered generators; their (hash, norm) pairs pass through LDS 2048 at a time, all
+// loads of a pass issued together (the kernel is a chain of memory latencies, not of work).
 __global__ __launch_bounds__(256) void k_dedupe(const double* __restrict__ cn2, const unsigned long long* __restrict__ hash, int k,
                                                 float* __restrict__ rn) {
     typedef __attribute__((ext_vector_type(2))) unsigned long long u64x2_t;
-    __shared__ u64x2_t tile[256];
+    constexpr int TILE = 2048, PER = TILE / 256;
+    __shared__ u64x2_t tile[TILE];
     __shared__ int copy_of_lower[64];
     const int tid = threadIdx.x, part = tid >> 6;
     const int j = blockIdx.x * 64 + (tid & 63), jj = min(j, k - 1);
     const u64x2_t mine = {hash[jj], (unsigned long long)__double_as_longlong(cn2[jj])};
     if (tid < 64) copy_of_lower[tid] = 0;
     bool copy = false;
-    for (int t0 = 0; t0 < int(blockIdx.x) * 64 + 64; t0 += 256) {
-        const int src = min(t0 + tid, k - 1);
+    const int below = int(blockIdx.x) * 64 + 64;               // generators this workgroup has to look at
+    for (int t0 = 0; t0 < below; t0 += TILE) {
+        u64x2_t v[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int src = min(t0 + tid + 256 * q, k - 1);
+            v[q] = u64x2_t{hash[src], (unsigned long long)__double_as_longlong(cn2[src])};
+        }
         __syncthreads();
-        tile[tid] = u64x2_t{hash[src], (unsigned long long)__double_as_longlong(cn2[src])};
+#pragma unroll
+        for (int q = 0; q < PER; ++q) tile[tid + 256 * q] = v[q];
         __syncthreads();
-        const int lim = min(256, j - t0);                      // only generators below j count
+        const int lim = min(TILE, j - t0);                     // only generators below j count
 #pragma unroll 8
         for (int q = part; q < lim; q += 4) {
             const u64x2_t o = tile[q];
