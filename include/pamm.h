@@ -228,7 +228,8 @@ const char *pamm_kernel_name(int id);
  *   piece_rows     positions of the sorted list per chunk of the contraction: a multiple of 16 in [16, 4096]
  *   contract_w     512-column groups per wave of the contraction: 1, 2 or 3
  *   sort_one_rows  largest b grouped by the single-workgroup counting sort: 1..16384
- *   small_tiles    1: the 256 x 256 tile kernel that C^T Btilde takes at large shapes with at least 512 generators is not used
+ *   small_tiles    the big-tile kernel that C^T Btilde takes at large shapes with at least 512 generators:
+ *                  1: not used; 2: used with 256 x 256 tiles (one workgroup per compute unit) instead of 256 x 128 (two)
  *
  * pamm_debug_bounded writes `count` consecutive draws of the sampler's bounded step (uniform on [0, range) by
  * rejection, as specified at pamm_sample_indices) from one generator seeded with `seed` into out_host, so that a

@@ -916,14 +916,52 @@ __global__ __launch_bounds__(256) void k_ctb(const u32x4_t* __restrict__ Ct, con
     }
 }
 
+// k_prep_rows: the operands of k_ctb_big, which takes them as they are stored (generator index across rows):
+//   Bp[j][:] = beta * (sum of generator j's partial rows), rounded once to bf16;   Cp[j][:] = C[j][:];
+// both with zero rows from k up to a whole number of 32-generator stages.  One thread per 16-byte chunk of a row.
+__global__ __launch_bounds__(256) void k_prep_rows(const u32x4_t* __restrict__ C, const float* __restrict__ partial,
+                                                   const int32_t* __restrict__ sbase, const int32_t* __restrict__ snum, int nch,
+                                                   int mch, int k, const int32_t* __restrict__ eta, int b,
+                                                   u32x4_t* __restrict__ Cp, u32x4_t* __restrict__ Bp) {
+    const int j = blockIdx.y;
+    const int x = blockIdx.x * 256 + threadIdx.x;               // chunk of the row: first those of Bp, then those of Cp
+    if (x < mch) {
+        u32x4_t out = {0u, 0u, 0u, 0u};
+        if (j < k) {
+            float beta = 1.f;                                   // normalisation factor of Sec. 3.2, as in k_prep
+            if (eta) {
+                const int dropped = *eta;
+                beta = dropped < b ? float(double(b) / double(b - dropped)) : 0.f;
+            }
+            const int base = sbase[j], np = snum[j];
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            const size_t row = size_t(mch) * 2;                 // a partial row in float4
+            const float4* src = reinterpret_cast<const float4*>(partial) + size_t(base) * row + size_t(x) * 2;
+            for (int q = 0; q < np; ++q) {
+                const float4 lo = src[size_t(q) * row], hi = src[size_t(q) * row + 1];
+                v[0] += lo.x; v[1] += lo.y; v[2] += lo.z; v[3] += lo.w;
+                v[4] += hi.x; v[5] += hi.y; v[6] += hi.z; v[7] += hi.w;
+            }
+            out = u32x4_t{pack_bf16(v[0] * beta, v[1] * beta), pack_bf16(v[2] * beta, v[3] * beta),
+                          pack_bf16(v[4] * beta, v[5] * beta), pack_bf16(v[6] * beta, v[7] * beta)};
+        }
+        Bp[size_t(j) * mch + x] = out;
+    } else if (x - mch < nch) {
+        const int c = x - mch;
+        Cp[size_t(j) * nch + c] = j < k ? C[size_t(j) * nch + c] : u32x4_t{0u, 0u, 0u, 0u};
+    }
+}
+
 // k_ctb_big: the same product for the shapes where the matrix cores are the limit (many generators, large weight
-// gradient; bf16 operands): 256 x 256 tiles on the shared main loop of pamm_tile256.h.  The operands' rows hold a whole
-// number of 32-generator stages (k_prep pads with zero generators).  Tile order, store layout and the bf16 packing are
-// those of k_ctb, over 4 x 4 accumulator fragments per wave.
-template <bool OUT16>
-__global__ __launch_bounds__(256) void k_ctb_big(const u32x4_t* __restrict__ Ct, const u32x4_t* __restrict__ Bt, int n, int m, int KC,
-                                                 int tiles_n, int tiles_m, int per_xcd, void* __restrict__ dWv) {
-    __shared__ u32x4_t lds[TileLds<4, 4>::kChunks];        // both operands come from L2 / Infinity Cache: equal rings
+// gradient; bf16 operands): 256 x 256 tiles on the main loop of pamm_tile256.h, with both operands as they are stored
+// (k' x n and k' x m, generator index across rows: the transposing LDS reads of gfx950 deliver the MFMA operands, so
+// nothing is transposed through memory); k' is a whole number of 32-generator stages (k_prep_rows pads with zero
+// rows).  Tile order, store layout and the bf16 packing are those of k_ctb, over 4 x 4 accumulator fragments per wave.
+template <bool OUT16, int FQ>
+__global__ __launch_bounds__(256, FQ == 2 ? 2 : 1) void k_ctb_big(const u32x4_t* __restrict__ Rp, const u32x4_t* __restrict__ Qp, int n, int m,
+                                                                  int kpad, int tiles_n, int tiles_m, int per_xcd, void* __restrict__ dWv) {
+    constexpr int NB = FQ == 2 ? 3 : 4;                    // stage buffers: what fits the LDS with 2 / 1 workgroups per CU
+    __shared__ u32x4_t lds[TileLds<NB, FQ>::kChunks];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
     const int wy = wave >> 1, wx = wave & 1;
     const int L = int(blockIdx.x % 8) * per_xcd + int(blockIdx.x / 8);
@@ -934,25 +972,25 @@ __global__ __launch_bounds__(256) void k_ctb_big(const u32x4_t* __restrict__ Ct,
         if (L < full * per_strip) { const int q = L % per_strip; tl = q / 8; tc = (L / per_strip) * 8 + q % 8; }
         else { const int q = L - full * per_strip; tl = q / rem; tc = full * 8 + q % rem; }
     }
-    const int l0 = tl * 256, c0 = tc * 256;
-    f32x16_t acc[4][4];
+    const int l0 = tl * 256, c0 = tc * (64 * FQ);
+    f32x16_t acc[4][FQ];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < FQ; ++q)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][q][i] = 0.f;
-    const TileSource src = tile_source(Ct, l0, n, size_t(KC), Bt, c0, m, size_t(KC));
-    tile_mainloop<4, 4>(lds, src, KC / 4, 0, acc);
+    const TileSource<FQ> src = tile_source<FQ>(Rp, l0, n, size_t(n / 8), Qp, c0, m, size_t(m / 8));
+    tile_mainloop<NB, FQ>(lds, src, kpad / 32, acc);
 
-    const int lw = l0 + wy * 128, cw = c0 + wx * 128;
-    const bool inside = l0 + 256 <= n && c0 + 256 <= m;      // uniform: a tile away from the edges stores unguarded
+    const int lw = l0 + wy * 128, cw = c0 + wx * (32 * FQ);
+    const bool inside = l0 + 256 <= n && c0 + 64 * FQ <= m;      // uniform: a tile away from the edges stores unguarded
     if constexpr (!OUT16) {
         float* __restrict__ dW = static_cast<float*>(dWv);
 #pragma unroll
         for (int fa = 0; fa < 4; ++fa)
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb) {
+            for (int fb = 0; fb < FQ; ++fb) {
                 const int c = cw + 32 * fb + r;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -966,7 +1004,7 @@ __global__ __launch_bounds__(256) void k_ctb_big(const u32x4_t* __restrict__ Ct,
 #pragma unroll
         for (int fa = 0; fa < 4; ++fa)
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb) {
+            for (int fb = 0; fb < FQ; ++fb) {
                 const int c = cw + 32 * fb + (r & ~1);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -1061,6 +1099,31 @@ static void launch_group_contract(const GradPlan& pl, const GradBuffers& g, cons
 template <typename TR>
 static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void* C, int n, int m, int k, const int32_t* eta, int b,
                             void* dW, bool out16, bool m_by_n, hipStream_t s) {
+    if (pl.big_tiles) {
+        if constexpr (std::is_same<TR, Bf16>::value) {
+            const int nch = n / 8, mch = m / 8, kpad = int(pl.kpad);
+            {
+                ScopedSpan span(kPrep, s);
+                hipLaunchKernelGGL(k_prep_rows, dim3((unsigned)((nch + mch + 255) / 256), (unsigned)kpad), dim3(256), 0, s,
+                                   (const u32x4_t*)C, g.partial, g.sbase, g.snum, nch, mch, k, eta, b, g.ct, g.bt);
+            }
+            // rows x cols of the result: n x m (O = A^T B), or m x n with the operands exchanged
+            const u32x4_t* rows_op = m_by_n ? g.bt : g.ct;
+            const u32x4_t* cols_op = m_by_n ? g.ct : g.bt;
+            const int nr = m_by_n ? m : n, nc = m_by_n ? n : m;
+            const bool wide = g_plan_override.small_tiles == 2;          // test hook: 256 x 256 tiles, one workgroup per CU
+            const int tiles_r = (nr + 255) / 256, tiles_c = wide ? (nc + 255) / 256 : (nc + 127) / 128;
+            const int per_xcd = (tiles_r * tiles_c + 7) / 8;
+            ScopedSpan span(kCtb, s);
+            const dim3 grid((unsigned)(per_xcd * 8));
+            auto launch = [&](auto kernel) {
+                hipLaunchKernelGGL(kernel, grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, kpad, tiles_r, tiles_c, per_xcd, dW);
+            };
+            if (wide) { if (out16) launch(k_ctb_big<true, 4>); else launch(k_ctb_big<false, 4>); }
+            else      { if (out16) launch(k_ctb_big<true, 2>); else launch(k_ctb_big<false, 2>); }
+        }
+        return;
+    }
     const int KC = int(pl.kpad) / TR::kPerChunk;
     const int blocks_m = (m + 63) / 64, blocks_n = (n + 63) / 64;
     {
@@ -1072,19 +1135,6 @@ static void launch_prep_ctb(const GradPlan& pl, const GradBuffers& g, const void
     const u32x4_t* rows_op = m_by_n ? g.bt : g.ct;
     const u32x4_t* cols_op = m_by_n ? g.ct : g.bt;
     const int nr = m_by_n ? m : n, nc = m_by_n ? n : m;
-    if (pl.big_tiles) {
-        if constexpr (std::is_same<TR, Bf16>::value) {
-            const int tiles_r = (nr + 255) / 256, tiles_c = (nc + 255) / 256;
-            const int per_xcd = (tiles_r * tiles_c + 7) / 8;
-            ScopedSpan span(kCtb, s);
-            const dim3 grid((unsigned)(per_xcd * 8));
-            if (out16)
-                hipLaunchKernelGGL((k_ctb_big<true>), grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, KC, tiles_r, tiles_c, per_xcd, dW);
-            else
-                hipLaunchKernelGGL((k_ctb_big<false>), grid, dim3(256), 0, s, rows_op, cols_op, nr, nc, KC, tiles_r, tiles_c, per_xcd, dW);
-        }
-        return;
-    }
     const int tiles_r = (nr + 127) / 128, tiles_c = (nc + 127) / 128;
     const int per_xcd = (tiles_r * tiles_c + 7) / 8;
     {

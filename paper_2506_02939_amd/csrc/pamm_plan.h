@@ -26,7 +26,7 @@ inline bool dtype_ok(pamm_dtype dt) { return dt == PAMM_F32 || dt == PAMM_BF16; 
 //   piece_rows     list positions per chunk in k_contract (a multiple of 16, 16..4096)
 //   contract_w     512-column groups per wave in k_contract (1..3)
 //   sort_one_rows  largest b sorted by the single-workgroup kernel (1..16384)
-//   small_tiles    1: never take the 256 x 256 tile kernel of the small product (k_ctb_big)
+//   small_tiles    1: never take the big-tile kernel of the small product (k_ctb_big); 2: take it with 256 x 256 tiles
 extern pamm_debug_plan g_plan_override;
 
 // ------------------------------------------------------------------------------------ compress
@@ -94,7 +94,7 @@ struct GradPlan {
     int wave_groups;      // W: 512-column groups per wave (1..3); a workgroup of 4 waves covers 4*W groups of a row
     int wg_cols;          // workgroups side by side along a row: ceil(col_groups / (4*W))
     int64_t kpad;         // k rounded up to a whole number of k_ctb stages (32 generators for bf16, 16 for fp32)
-    bool big_tiles;       // C^T Btilde on 256 x 256 tiles (k_ctb_big): bf16, many generators, a large weight gradient
+    bool big_tiles;       // C^T Btilde on 256 x 128 tiles (k_ctb_big): bf16, many generators, a large weight gradient
     int slice_rows;       // rows per slice of the counting sort (1024 or 4096)
     int64_t nslices;      // ceil(b / slice_rows)
     size_t off_list, off_hdr, off_sbase, off_snum, off_table, off_partial, off_ct, off_bt, total;
@@ -129,10 +129,10 @@ inline pamm_status plan_grad(int64_t b, int64_t n, int64_t k, int64_t m, pamm_dt
         p->chunks = (even > longest ? even : longest) + 1;
     }
     p->nslots = p->chunks + k;
-    // The product C^T Btilde runs on 256 x 256 tiles where the matrix cores are its limit: bf16, at least 512 generators
-    // (with fewer the product is bound by the write of the result, which the small tiles overlap better) and at least
-    // two such tiles per compute unit.
-    p->big_tiles = dt == PAMM_BF16 && k >= 512 && ((n + 255) / 256) * ((m + 255) / 256) >= 2 * kNumCU && g_plan_override.small_tiles == 0;
+    // The product C^T Btilde runs on big tiles (k_ctb_big) where the matrix cores are its limit: bf16, at least 512
+    // generators (with fewer the product is bound by the write of the result, which the small tiles overlap better) and
+    // a result of at least two 256 x 256 blocks per compute unit.
+    p->big_tiles = dt == PAMM_BF16 && k >= 512 && ((n + 255) / 256) * ((m + 255) / 256) >= 2 * kNumCU && g_plan_override.small_tiles != 1;
     const int64_t stage_gens = 4 * per_chunk(dt);      // generators per stage: 32 (bf16) or 16 (fp32)
     p->kpad = (k + stage_gens - 1) / stage_gens * stage_gens;
     // Counting sort of the rows by generator: short slices spread the scattered list writes over many CUs, but every

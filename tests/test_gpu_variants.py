@@ -203,13 +203,15 @@ def test_near_ties_on_rows_far_from_every_generator(pamm, oracle, dn, n, cos):
     assert wrong == 0
 
 
-# ------------------------------------------------------------------------------------------ the 256 x 256 tiles of C^T Btilde
+# ------------------------------------------------------------------------------------------ the big tiles of C^T Btilde
 
+@pytest.mark.parametrize("tile", ["256x128", "256x256"])
 @pytest.mark.parametrize("form", ["f32", "bf16", "f32_m_by_n", "bf16_m_by_n"])
-def test_big_tiles_of_the_small_product(pamm, oracle, form):
-    """At least 512 generators and at least 512 tiles of 256 x 256: the product C^T Btilde takes the kernel built on the
-    shared 256 x 256 main loop.  Ragged edges in both directions, 520 generators (padded to 640 with zero generators), all
-    four output forms, against the oracle element by element."""
+def test_big_tiles_of_the_small_product(pamm, oracle, form, tile):
+    """At least 512 generators and a weight gradient of at least 512 blocks of 256 x 256: the product C^T Btilde takes
+    the kernel built on the big-tile main loop, on 256 x 128 tiles (two workgroups per compute unit: what the library
+    picks) and on 256 x 256 tiles (one; forced).  Ragged edges in both directions, 520 generators (padded to 544 with
+    zero rows), all four output forms, against the oracle element by element."""
     w = workloads.scaled(workloads.WORKLOADS["llama7b_k1024"], name="big_tiles", seqs=2, seq_len=1024, n=4000, m=8200, k=520, centres=300)
     X, dY = workloads.generate(w)
     got = pamm.compress(X.cuda(), w.k, seed=3)
@@ -220,8 +222,12 @@ def test_big_tiles_of_the_small_product(pamm, oracle, form):
     _, O = oracle.grad(C64, f, a, dY)
     _, O_abs = oracle.grad(np.abs(C64), f, np.abs(a), dY.abs())
     kw = dict(out_dtype=torch.bfloat16 if form.startswith("bf16") else torch.float32, transposed=form.endswith("m_by_n"))
-    dW = pamm.grad(got.C, got.f, got.alpha, dY.cuda(), **kw)
-    torch.cuda.synchronize()
+    pamm.debug_set_plan(small_tiles=2 if tile == "256x256" else 0)
+    try:
+        dW = pamm.grad(got.C, got.f, got.alpha, dY.cuda(), **kw)
+        torch.cuda.synchronize()
+    finally:
+        pamm.debug_set_plan()
     res = dW.float().cpu().numpy().astype(np.float64)
     if kw["transposed"]:
         res = res.T
