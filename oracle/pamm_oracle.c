@@ -59,6 +59,10 @@
  *                unbiasedness over all k-subsets are checked by enumeration; error bound of
  *                Sec. 3.2.1 with dropped rows.
  *
+ *   sketch       (the random-projection baseline of Sec. 4.6, at the end of this file; tests/test_oracle_sketch.py)
+ *                P = identity gives S = A and exactly A^T B; an orthogonal P gives A^T B; coordinate
+ *                selection; the rank-one closed form p p^T A^T B; unbiasedness over Gaussian P.
+ *
  * Element types: 0 = IEEE binary32, 1 = bfloat16 (raw 16-bit patterns),
  * 2 = IEEE binary64.  Decoding to double is exact for all three.
  * All matrices are row-major and contiguous.
@@ -310,6 +314,61 @@ int pamm_oracle_grad(const double *C, const int32_t *f, const double *alpha,
             for (int64_t c = 0; c < m; ++c) out[c] += cjl * bt[c];
         }
         for (int64_t c = 0; c < m; ++c) out[c] *= beta;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------ comparison: low-rank sketch */
+
+/*
+ * The random-projection baseline of the ablation (Sec. 4.6): instead of (C, f, alpha) the layer keeps the
+ * sketch S = A P of its input, P an n x r random matrix with E[P P^T] = I, and the weight gradient is
+ * estimated as P (S^T B) = (P P^T) A^T B.  The random numbers are an input: P is passed through its
+ * transpose Pt (r x n, row-major), so that row j of Pt is the j-th sketch direction.
+ *
+ * pamm_oracle_sketch:       S[i][j] = <A_i, Pt_j>                       (b x r doubles, not rounded)
+ * pamm_oracle_sketch_grad:  G = S^T B  (r x m),  O = Pt^T G  (n x m),   rows added in increasing i / j.
+ * The stored sketch has an element type of its own (sdtype): the caller rounds S to what the layer keeps.
+ */
+int pamm_oracle_sketch(const void *A, int dtype, const void *Pt, int pdtype,
+                       int64_t b, int64_t n, int64_t r, double *S)
+{
+    if (!A || !Pt || !S || b < 1 || n < 1 || r < 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < b; ++i)
+        for (int64_t j = 0; j < r; ++j) {
+            double d = 0.0;
+            for (int64_t l = 0; l < n; ++l)
+                d += decode(A, dtype, (size_t)i * (size_t)n + (size_t)l) * decode(Pt, pdtype, (size_t)j * (size_t)n + (size_t)l);
+            S[i * r + j] = d;
+        }
+    return 0;
+}
+
+int pamm_oracle_sketch_grad(const void *Pt, int pdtype, const void *S, int sdtype,
+                            const void *B, int dtype,
+                            int64_t b, int64_t n, int64_t r, int64_t m,
+                            double *G, double *O)
+{
+    if (!Pt || !S || !B || !G || !O || b < 1 || n < 1 || r < 1 || m < 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < r; ++j) {
+        double *g = G + j * m;
+        for (int64_t c = 0; c < m; ++c) g[c] = 0.0;
+        for (int64_t i = 0; i < b; ++i) {
+            double s = decode(S, sdtype, (size_t)i * (size_t)r + (size_t)j);
+            for (int64_t c = 0; c < m; ++c) g[c] += s * decode(B, dtype, (size_t)i * (size_t)m + (size_t)c);
+        }
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t l = 0; l < n; ++l) {
+        double *out = O + l * m;
+        for (int64_t c = 0; c < m; ++c) out[c] = 0.0;
+        for (int64_t j = 0; j < r; ++j) {
+            double p = decode(Pt, pdtype, (size_t)j * (size_t)n + (size_t)l);     /* P[l][j] */
+            const double *g = G + j * m;
+            for (int64_t c = 0; c < m; ++c) out[c] += p * g[c];
+        }
     }
     return 0;
 }

@@ -52,6 +52,10 @@ def _load():
         lib.pamm_oracle_grad.restype = ctypes.c_int
         lib.pamm_oracle_bounded.argtypes = [ctypes.c_uint64, ctypes.c_uint64, i64, ctypes.POINTER(ctypes.c_uint64)]
         lib.pamm_oracle_bounded.restype = ctypes.c_int
+        lib.pamm_oracle_sketch.argtypes = [vp, ctypes.c_int, vp, ctypes.c_int, i64, i64, i64, f64p]
+        lib.pamm_oracle_sketch.restype = ctypes.c_int
+        lib.pamm_oracle_sketch_grad.argtypes = [vp, ctypes.c_int, vp, ctypes.c_int, vp, ctypes.c_int, i64, i64, i64, i64, f64p, f64p]
+        lib.pamm_oracle_sketch_grad.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -182,3 +186,38 @@ def grad(C, f, alpha, dY, beta: float = 1.0):
     if rc != 0:
         raise ValueError("pamm_oracle_grad: bad arguments")
     return Bt, O
+
+
+def sketch(X, Pt) -> np.ndarray:
+    """S = X P for P given through its transpose Pt (r x n): S[i][j] = <X_i, Pt_j>, b x r float64, not rounded
+    (the random-projection baseline of Sec. 4.6)."""
+    x, xcode = as_raw(X)
+    p, pcode = as_raw(Pt)
+    b, n = x.shape
+    r, n2 = p.shape
+    assert n2 == n
+    S = np.empty((b, r), dtype=np.float64)
+    rc = _load().pamm_oracle_sketch(x.ctypes.data_as(ctypes.c_void_p), xcode, p.ctypes.data_as(ctypes.c_void_p), pcode,
+                                    b, n, r, _p(S, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("pamm_oracle_sketch: bad arguments")
+    return S
+
+
+def sketch_grad(Pt, S, dY):
+    """The sketch's estimate of X^T dY: returns (G = S^T dY, r x m; O = P G = Pt^T G, n x m), both float64.  S is the
+    stored sketch in its own element type (numpy float32 / float64 / bfloat16 bits, or a CPU torch tensor)."""
+    p, pcode = as_raw(Pt)
+    s, scode = as_raw(S)
+    y, ycode = as_raw(dY)
+    r, n = p.shape
+    b, m = y.shape
+    assert s.shape == (b, r)
+    G = np.empty((r, m), dtype=np.float64)
+    O = np.empty((n, m), dtype=np.float64)
+    rc = _load().pamm_oracle_sketch_grad(p.ctypes.data_as(ctypes.c_void_p), pcode, s.ctypes.data_as(ctypes.c_void_p), scode,
+                                         y.ctypes.data_as(ctypes.c_void_p), ycode, b, n, r, m,
+                                         _p(G, ctypes.c_double), _p(O, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("pamm_oracle_sketch_grad: bad arguments")
+    return G, O

@@ -24,6 +24,7 @@ def _pins(name):
 eps_pins = _pins("test_oracle_eps")
 pins = _pins("test_oracle_pins")
 sampler_pins = _pins("test_oracle_sampler")
+sketch_pins = _pins("test_oracle_sketch")
 
 
 def _load_mutant(tmp_path, name, old, new):
@@ -104,6 +105,18 @@ MUTANTS = [
      [lambda o: eps_pins.test_beta_makes_column_row_sampling_unbiased(o), lambda o: eps_pins.test_zero_tolerance_is_uniform_column_row_sampling(o)]),
     ("beta_not_applied", "for (int64_t c = 0; c < m; ++c) out[c] *= beta;", ";",
      [lambda o: eps_pins.test_beta_makes_column_row_sampling_unbiased(o)]),
+    ("sketch_with_transposed_projection", "d += decode(A, dtype, (size_t)i * (size_t)n + (size_t)l) * decode(Pt, pdtype, (size_t)j * (size_t)n + (size_t)l);",
+     "d += decode(A, dtype, (size_t)i * (size_t)n + (size_t)l) * decode(Pt, pdtype, (size_t)((j * n + l) % r) * (size_t)n + (size_t)((j * n + l) / r % n));",
+     [lambda o: sketch_pins.test_orthogonal_projection_gives_the_exact_product(o), lambda o: sketch_pins.test_coordinate_selection(o)]),
+    ("sketch_grad_takes_the_wrong_sketch_column", "double s = decode(S, sdtype, (size_t)i * (size_t)r + (size_t)j);",
+     "double s = decode(S, sdtype, (size_t)i * (size_t)r + (size_t)(r - 1 - j));",
+     [lambda o: sketch_pins.test_coordinate_selection(o), lambda o: sketch_pins.test_orthogonal_projection_gives_the_exact_product(o)]),
+    ("sketch_grad_last_product_transposed", "double p = decode(Pt, pdtype, (size_t)j * (size_t)n + (size_t)l);     /* P[l][j] */",
+     "double p = decode(Pt, pdtype, (size_t)((l * r + j) / n % r) * (size_t)n + (size_t)((l * r + j) % n));",
+     [lambda o: sketch_pins.test_orthogonal_projection_gives_the_exact_product(o), lambda o: sketch_pins.test_coordinate_selection(o)]),
+    ("sketch_grad_drops_the_sketch", "g[c] += s * decode(B, dtype, (size_t)i * (size_t)m + (size_t)c);",
+     "g[c] += decode(B, dtype, (size_t)i * (size_t)m + (size_t)c);",
+     [lambda o: sketch_pins.test_rank_one_closed_form(o), lambda o: sketch_pins.test_identity_projection_keeps_everything(o)]),
 ]
 
 
