@@ -204,6 +204,26 @@ pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
                           float *Btilde, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The random-projection baseline of the ablation (Sec. 4.6, the comparison with a low-rank sketch of the activation):
+ * instead of (C, f, alpha) the layer keeps S = X P, with P an n x r random matrix with E[P P^T] = I, and estimates
+ * the weight gradient as P (S^T dY).  On the same harness as the calls above, for comparisons at equal memory
+ * (the sketch holds b r numbers, PAMM's compression k n + 2 b).  The random numbers are the caller's: P is passed
+ * through its transpose Pt (r x n, row-major, element type dt), row j being the j-th direction of the sketch.
+ *
+ *   pamm_sketch        S (b x r, element type dt) = X Pt^T, fp32 accumulation, rounded once to dt.  No workspace.
+ *   pamm_sketch_grad   dW (n x m fp32) = Pt^T G, G = S^T dY (r x m): G is accumulated in fp32 over chunks of tokens on
+ *                      the matrix cores while dY streams once, rounded once to dt, and multiplied by the kernels of
+ *                      pamm_grad's last step.  PAMM_BF16 only (PAMM_F32: PAMM_ERR_UNSUPPORTED).
+ * r is a multiple of 8 (of 4 for PAMM_F32 in pamm_sketch), r <= min(b, 128); other sizes as above.
+ */
+size_t pamm_sketch_grad_workspace(int64_t b, int64_t n, int64_t r, int64_t m, pamm_dtype dt);
+pamm_status pamm_sketch(const void *X, const void *Pt, int64_t b, int64_t n, int64_t r, pamm_dtype dt,
+                        void *S, void *stream);
+pamm_status pamm_sketch_grad(const void *Pt, const void *S, const void *dY,
+                             int64_t b, int64_t n, int64_t r, int64_t m, pamm_dtype dt,
+                             float *dW, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (the paper reports its own cost per operation in App. F, Tables 6-7).
  * Between pamm_profile_begin() and pamm_profile_end() every kernel the library launches is bracketed by
  * a pair of HIP events on its launch stream (events are created per launch: not for use on a hot path).
@@ -211,7 +231,7 @@ pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
  * elapsed milliseconds and the number of launches; both arrays are HOST pointers of PAMM_NUM_KERNELS
  * entries.  pamm_kernel_name gives the name of a kernel id ("" if out of range).  Process-wide state.
  */
-#define PAMM_NUM_KERNELS 8
+#define PAMM_NUM_KERNELS 10
 pamm_status pamm_profile_begin(void);
 pamm_status pamm_profile_end(double *ms_total, int64_t *launches);
 const char *pamm_kernel_name(int id);

@@ -32,6 +32,11 @@ extern "C" size_t pamm_grad_workspace(int64_t b, int64_t n, int64_t k, int64_t m
     return plan_grad(b, n, k, m, dt, &p) == PAMM_OK ? p.total : 0;
 }
 
+extern "C" size_t pamm_sketch_grad_workspace(int64_t b, int64_t n, int64_t r, int64_t m, pamm_dtype dt) {
+    SketchGradPlan p;
+    return plan_sketch_grad(b, n, r, m, dt, &p) == PAMM_OK ? p.total : 0;
+}
+
 namespace {
 
 struct SplitMix64 {
@@ -88,7 +93,7 @@ extern "C" pamm_status pamm_debug_bounded(uint64_t seed, uint64_t range, int64_t
 }
 
 extern "C" const char* pamm_kernel_name(int id) {
-    static const char* names[kNumKernels] = {"k_gather", "k_score", "k_finalize", "k_group", "k_contract", "k_prep", "k_ctb", "k_piece_sum"};
+    static const char* names[kNumKernels] = {"k_gather", "k_score", "k_finalize", "k_group", "k_contract", "k_prep", "k_ctb", "k_piece_sum", "k_sketch", "k_sketch_contract"};
     return (id >= 0 && id < kNumKernels) ? names[id] : "";
 }
 

@@ -350,12 +350,16 @@ __device__ __forceinline__ void name_fragment(const f32x16_t (&acc)[NA][NQ], int
 // loads, stashes and stage stores of the super-step are placed between those groups.
 // FUSED (one column block holds every generator): the epilogue takes the final decision itself and writes f and
 // alpha; otherwise it writes one candidate record per token and column block for k_finalize.
-template <typename TR, int TG, int TT, int NW, bool ALIGNED, bool FUSED>
+// SKETCH: the same walk for the random-projection baseline (Sec. 4.6): the rows of C are the directions of the sketch,
+// nothing is decided, and the epilogue stores the dot products themselves, S[i][j] = <X_i, C_j>, rounded once to the
+// element type (rn, cn2, hash, cand, f, alpha, eta are not used).
+template <typename TR, int TG, int TT, int NW, bool ALIGNED, bool FUSED, bool SKETCH = false>
 __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ C,
                                                    const float* __restrict__ rn, const double* __restrict__ cn2,
                                                    const unsigned long long* __restrict__ hash, int b, int nch, int k, int ncb,
                                                    u32x4_t* __restrict__ cand, int32_t* __restrict__ f, float* __restrict__ alpha,
-                                                   double keep, int32_t* __restrict__ eta) {
+                                                   double keep, int32_t* __restrict__ eta, void* __restrict__ sketch = nullptr) {
+    static_assert(!(SKETCH && FUSED), "the sketch decides nothing");
     constexpr int NT = 64 * NW;
     const bool want_norm = keep >= 0.0;           // a finite tolerance: ||X_i||^2 is needed (uniform over the grid)
     constexpr int GB = 32 * TG;          // generators per column block
@@ -400,11 +404,13 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     constexpr int GPT = (GB + NT - 1) / NT;       // generators per thread
     float rn_reg[GPT];
     unsigned long long hash_reg[GPT], norm_reg[GPT];
+    if constexpr (!SKETCH) {
 #pragma unroll
-    for (int q = 0; q < GPT; ++q) {
-        const int jj = min(gen0 + tid + NT * q, k - 1);
-        rn_reg[q] = rn[jj];
-        if (FUSED) { hash_reg[q] = hash[jj]; norm_reg[q] = (unsigned long long)__double_as_longlong(cn2[jj]); }
+        for (int q = 0; q < GPT; ++q) {
+            const int jj = min(gen0 + tid + NT * q, k - 1);
+            rn_reg[q] = rn[jj];
+            if (FUSED) { hash_reg[q] = hash[jj]; norm_reg[q] = (unsigned long long)__double_as_longlong(cn2[jj]); }
+        }
     }
 
     // coalesced view of this wave's tokens: load i of fragment tt covers rows 8i .. 8i+7, lane L the row 8i + L/8
@@ -505,12 +511,14 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
     load_c(0, 0);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d) load_x(xr[d], d);
+    if constexpr (!SKETCH) {
 #pragma unroll
-    for (int q = 0; q < GPT; ++q) {
-        const int t = tid + NT * q;
-        if (t < GB) {
-            lds_rn[t] = gen0 + t < k ? rn_reg[q] : 0.f;
-            if (FUSED) { lds_hash[t] = hash_reg[q]; lds_norm[t] = norm_reg[q]; }
+        for (int q = 0; q < GPT; ++q) {
+            const int t = tid + NT * q;
+            if (t < GB) {
+                lds_rn[t] = gen0 + t < k ? rn_reg[q] : 0.f;
+                if (FUSED) { lds_hash[t] = hash_reg[q]; lds_norm[t] = norm_reg[q]; }
+            }
         }
     }
     if (FUSED) {
@@ -605,6 +613,34 @@ __global__ __launch_bounds__(64 * NW) void k_score(const u32x4_t* __restrict__ X
                 wave_lds_sync();                             // the stashed tokens are read by other lanes of this wave
             }
         }
+    }
+
+    if constexpr (SKETCH) {
+        // register i of fragment a belongs to direction gen0 + 32 a + 8 (i / 4) + 4 g + i % 4 and to token r of the
+        // fragment: four consecutive directions of one token make one 8- or 16-byte store
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const int row = row_base + 32 * tt + r;
+#pragma unroll
+            for (int a = 0; a < TG; ++a)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j0 = gen0 + 32 * a + 8 * q + 4 * g;
+                    if (row < b && j0 < k) {
+                        const float v0 = acc[a][tt][4 * q], v1 = acc[a][tt][4 * q + 1], v2 = acc[a][tt][4 * q + 2],
+                                    v3 = acc[a][tt][4 * q + 3];
+                        if constexpr (TR::kElemBytes == 2) {
+                            uint2 out;
+                            out.x = pack_bf16(v0, v1);
+                            out.y = pack_bf16(v2, v3);
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(sketch) + size_t(row) * k + j0) = out;
+                        } else {
+                            *reinterpret_cast<float4*>(static_cast<float*>(sketch) + size_t(row) * k + j0) = make_float4(v0, v1, v2, v3);
+                        }
+                    }
+                }
+        }
+        return;
     }
 
     // Epilogue: the scan runs on the accumulator registers themselves (scan_fragment).  Per wave a little LDS (all tiles
@@ -796,6 +832,34 @@ static void launch_score(const CompressPlan& pl, const ScoreArgs& a, hipStream_t
     else launch_score_blocks<TR, true>(pl, a, s);
 }
 
+// The sketch S = X Pt^T on the walk of the score kernel; the plan is the one the score kernel would take for r generators.
+template <typename TR, int TG, int NW>
+static void launch_sketch_cfg(const CompressPlan& pl, const void* X, const void* Pt, int b, int nch, int r, void* S, hipStream_t s) {
+    dim3 grid((unsigned)(pl.ncb > 1 ? (pl.row_tiles + 7) / 8 * 8 * pl.ncb : pl.row_tiles));
+#define PAMM_LAUNCH_SKETCH(AL) \
+    hipLaunchKernelGGL((k_score<TR, TG, 1, NW, AL, false, true>), grid, dim3(64 * NW), 0, s, (const u32x4_t*)X, (const u32x4_t*)Pt, \
+                       (const float*)nullptr, (const double*)nullptr, (const unsigned long long*)nullptr, b, nch, r, pl.ncb,        \
+                       (u32x4_t*)nullptr, (int32_t*)nullptr, (float*)nullptr, -1.0, (int32_t*)nullptr, S)
+    if (nch % 8 == 0) PAMM_LAUNCH_SKETCH(true);
+    else PAMM_LAUNCH_SKETCH(false);
+#undef PAMM_LAUNCH_SKETCH
+}
+
+template <typename TR>
+static void launch_sketch(const CompressPlan& pl, const void* X, const void* Pt, int b, int nch, int r, void* S, hipStream_t s) {
+    // r <= 128: at most four fragments per wave; the waves per workgroup are the plan's
+#define PAMM_SKETCH_NW(TGV)                                                             \
+    do {                                                                                \
+        if (pl.nw == 8) launch_sketch_cfg<TR, TGV, 8>(pl, X, Pt, b, nch, r, S, s);      \
+        else if (pl.nw == 4) launch_sketch_cfg<TR, TGV, 4>(pl, X, Pt, b, nch, r, S, s); \
+        else launch_sketch_cfg<TR, TGV, 2>(pl, X, Pt, b, nch, r, S, s);                 \
+    } while (0)
+    if (pl.tg == 1) PAMM_SKETCH_NW(1);
+    else if (pl.tg == 2) PAMM_SKETCH_NW(2);
+    else PAMM_SKETCH_NW(4);
+#undef PAMM_SKETCH_NW
+}
+
 // idx_dev: the generators' row numbers in device memory, or NULL: then idx_host holds them (host memory, only read
 // during the call) and they travel in argument blocks.
 template <typename TR>
@@ -894,4 +958,18 @@ extern "C" pamm_status pamm_compress_eps(const void* X, int64_t b, int64_t n, in
     double keep;
     if (!eta || !aligned4(eta) || keep_of(eps, &keep) != PAMM_OK) return PAMM_ERR_INVALID_ARG;
     return compress_seed_impl(X, b, n, k, seed, keep, dt, C, f, alpha, eta, ws, ws_bytes, stream);
+}
+
+extern "C" pamm_status pamm_sketch(const void* X, const void* Pt, int64_t b, int64_t n, int64_t r, pamm_dtype dt, void* S,
+                                   void* stream) {
+    pamm_status st = check_sketch_args(X, Pt, b, n, r, dt, S);
+    if (st != PAMM_OK) return st;
+    CompressPlan pl;
+    st = plan_compress(b, n, r, dt, &pl);
+    if (st != PAMM_OK) return st;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    ScopedSpan span(kSketch, s);
+    if (dt == PAMM_BF16) launch_sketch<Bf16>(pl, X, Pt, int(b), int(n / 8), int(r), S, s);
+    else launch_sketch<F32>(pl, X, Pt, int(b), int(n / 4), int(r), S, s);
+    return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
 }

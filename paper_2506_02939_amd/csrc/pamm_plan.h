@@ -204,4 +204,76 @@ inline pamm_status check_grad_args(const void* C, const void* f, const void* alp
     return PAMM_OK;
 }
 
+// -------------------------------------------------------------------------------------- sketch
+
+constexpr int64_t kMaxSketch = 128;        // widest sketch: four 32-wide fragments next to four of dY in a wave's registers
+
+inline pamm_status check_sketch_sizes(int64_t b, int64_t n, int64_t r, pamm_dtype dt) {
+    if (!dtype_ok(dt)) return PAMM_ERR_UNSUPPORTED;
+    if (b < 1 || n < 1 || r < 1 || r > b || b >= (int64_t(1) << 31) || n >= (int64_t(1) << 31)) return PAMM_ERR_INVALID_ARG;
+    if (r > kMaxSketch || n % per_chunk(dt) != 0 || r % per_chunk(dt) != 0) return PAMM_ERR_UNSUPPORTED;
+    return PAMM_OK;
+}
+
+// pamm_sketch_grad: G = S^T dY in partial rows (one per sketch column and chunk of tokens), then the small product of
+// ApproxMM with P^T in the place of C and the sketch columns in the place of the generators.
+struct SketchGradPlan {
+    GradPlan g;           // what the small product reads: kpad, big_tiles and the offsets of sbase, snum, partial, ct, bt
+    int nr;               // 32-wide fragments of the sketch: ceil(r / 32)
+    int col_groups;       // ceil(m / 512): a workgroup takes 512 columns of dY
+    int64_t chunk_rows;   // tokens per chunk, a multiple of 32
+    int64_t chunks;
+    size_t off_zero, total;
+};
+
+inline pamm_status plan_sketch_grad(int64_t b, int64_t n, int64_t r, int64_t m, pamm_dtype dt, SketchGradPlan* p) {
+    pamm_status st = check_sketch_sizes(b, n, r, dt);
+    if (st != PAMM_OK) return st;
+    if (dt != PAMM_BF16) return PAMM_ERR_UNSUPPORTED;      // the transposing LDS reads exist for 16-bit elements
+    if (m < 1 || m >= (int64_t(1) << 31)) return PAMM_ERR_INVALID_ARG;
+    if (m % 8 != 0) return PAMM_ERR_UNSUPPORTED;
+    p->nr = int((r + 31) / 32);
+    p->col_groups = int((m + 511) / 512);
+    // two workgroups per compute unit in all (each streams its chunk of 512 columns; the LDS ring admits one at a time)
+    const int64_t want = (2 * kNumCU + p->col_groups - 1) / p->col_groups;
+    int64_t rows = (b + want - 1) / want;
+    rows = (rows + 31) / 32 * 32;
+    p->chunk_rows = rows < 128 ? 128 : rows;
+    p->chunks = (b + p->chunk_rows - 1) / p->chunk_rows;
+    GradPlan& g = p->g;
+    g = GradPlan{};
+    g.big_tiles = false;
+    g.kpad = (r + 31) / 32 * 32;
+    size_t o = 0;
+    p->off_zero = o;    o = align_up(o + 16, 256);
+    g.off_sbase = o;    o = align_up(o + size_t(r) * 4, 256);
+    g.off_snum = o;     o = align_up(o + size_t(r) * 4, 256);
+    g.off_partial = o;  o = align_up(o + size_t(r) * size_t(p->chunks) * size_t(m) * 4, 256);
+    g.off_ct = o;       o = align_up(o + size_t(n) * size_t(g.kpad) * 2, 256);
+    g.off_bt = o;       o = align_up(o + size_t(m) * size_t(g.kpad) * 2, 256);
+    g.off_list = g.off_hdr = g.off_table = 0;      // not used
+    g.total = o;
+    p->total = o;
+    return PAMM_OK;
+}
+
+inline pamm_status check_sketch_args(const void* X, const void* Pt, int64_t b, int64_t n, int64_t r, pamm_dtype dt, const void* S) {
+    pamm_status st = check_sketch_sizes(b, n, r, dt);
+    if (st != PAMM_OK) return st;
+    if (!X || !Pt || !S) return PAMM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(Pt) || !aligned16(S)) return PAMM_ERR_INVALID_ARG;
+    return PAMM_OK;
+}
+
+inline pamm_status check_sketch_grad_args(const void* Pt, const void* S, const void* dY, int64_t b, int64_t n, int64_t r, int64_t m,
+                                          pamm_dtype dt, const void* dW, const void* ws, size_t ws_bytes, SketchGradPlan* pl) {
+    pamm_status st = plan_sketch_grad(b, n, r, m, dt, pl);
+    if (st != PAMM_OK) return st;
+    if (!Pt || !S || !dY || !dW) return PAMM_ERR_INVALID_ARG;
+    if (!aligned16(Pt) || !aligned16(S) || !aligned16(dY) || !aligned16(dW)) return PAMM_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < pl->total) return PAMM_ERR_WORKSPACE;
+    if (!aligned16(ws)) return PAMM_ERR_INVALID_ARG;
+    return PAMM_OK;
+}
+
 }  // namespace pamm

@@ -9,7 +9,7 @@
 
 namespace pamm {
 
-enum KernelId { kGather = 0, kScore, kFinalize, kGroup, kContract, kPrep, kCtb, kPieceSum, kNumKernels };
+enum KernelId { kGather = 0, kScore, kFinalize, kGroup, kContract, kPrep, kCtb, kPieceSum, kSketch, kSketchContract, kNumKernels };
 
 struct Profiler {
     bool on = false;

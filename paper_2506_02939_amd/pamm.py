@@ -24,10 +24,11 @@ EXPORTS = [
     "pamm_status_string", "pamm_compress_workspace", "pamm_grad_workspace", "pamm_sample_indices",
     "pamm_compress", "pamm_compress_idx", "pamm_compress_eps", "pamm_compress_idx_eps", "pamm_grad", "pamm_grad_eps",
     "pamm_grad_out", "pamm_grad_static", "pamm_contract",
+    "pamm_sketch_grad_workspace", "pamm_sketch", "pamm_sketch_grad",
     "pamm_profile_begin", "pamm_profile_end", "pamm_kernel_name",
     "pamm_debug_set_plan", "pamm_debug_bounded",
 ]
-NUM_KERNELS = 8
+NUM_KERNELS = 10
 
 
 class PammError(RuntimeError):
@@ -69,6 +70,12 @@ def _load() -> ctypes.CDLL:
     lib.pamm_grad_static.restype = ci
     lib.pamm_contract.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     lib.pamm_contract.restype = ci
+    lib.pamm_sketch_grad_workspace.argtypes = [i64, i64, i64, i64, ci]
+    lib.pamm_sketch_grad_workspace.restype = sz
+    lib.pamm_sketch.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp]
+    lib.pamm_sketch.restype = ci
+    lib.pamm_sketch_grad.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, vp, vp, sz, vp]
+    lib.pamm_sketch_grad.restype = ci
     lib.pamm_profile_begin.argtypes = []
     lib.pamm_profile_begin.restype = ci
     lib.pamm_profile_end.argtypes = [vp, vp]
@@ -229,6 +236,40 @@ def grad_static(C: torch.Tensor, f: torch.Tensor, alpha: torch.Tensor, dY: torch
     st = lib.pamm_grad_static(_dev(C, "C"), _dev(f, "f"), _dev(alpha, "alpha"), _dev(dY, "dY"), b, n, k, m, _dtype_code(dY),
                               _dev(out, "out"), _stream())
     _check(st, "pamm_grad_static")
+    return out
+
+
+def sketch_grad_workspace(b: int, n: int, r: int, m: int, dtype: int) -> int:
+    return int(lib.pamm_sketch_grad_workspace(b, n, r, m, dtype))
+
+
+def sketch(X: torch.Tensor, Pt: torch.Tensor, *, out: torch.Tensor | None = None) -> torch.Tensor:
+    """pamm_sketch: S (b x r, element type of X) = X Pt^T, the sketch the random-projection baseline keeps."""
+    b, n = X.shape
+    r, n2 = Pt.shape
+    if n2 != n or Pt.dtype != X.dtype:
+        raise PammError(PAMM_ERR_INVALID_ARG, "Pt must be r x n of X's element type")
+    if out is None:
+        out = torch.empty(b, r, dtype=X.dtype, device=X.device)
+    st = lib.pamm_sketch(_dev(X, "X"), _dev(Pt, "Pt"), b, n, r, _dtype_code(X), _dev(out, "out"), _stream())
+    _check(st, "pamm_sketch")
+    return out
+
+
+def sketch_grad(Pt: torch.Tensor, S: torch.Tensor, dY: torch.Tensor, *, out: torch.Tensor | None = None,
+                ws: torch.Tensor | None = None) -> torch.Tensor:
+    """pamm_sketch_grad: dW (n x m, fp32) = Pt^T (S^T dY), the baseline's estimate of X^T dY."""
+    r, n = Pt.shape
+    b, m = dY.shape
+    if tuple(S.shape) != (b, r) or S.dtype != dY.dtype or Pt.dtype != dY.dtype:
+        raise PammError(PAMM_ERR_INVALID_ARG, "S must be b x r, and Pt, S, dY of one element type")
+    dt = _dtype_code(dY)
+    if out is None:
+        out = torch.empty(n, m, dtype=torch.float32, device=dY.device)
+    ws = _workspace(sketch_grad_workspace(b, n, r, m, dt), dY.device, ws)
+    st = lib.pamm_sketch_grad(_dev(Pt, "Pt"), _dev(S, "S"), _dev(dY, "dY"), b, n, r, m, dt, _dev(out, "out"), ws.data_ptr(),
+                              ws.numel(), _stream())
+    _check(st, "pamm_sketch_grad")
     return out
 
 

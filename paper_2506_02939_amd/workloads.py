@@ -15,6 +15,7 @@ Recipe (all draws from one ``torch.Generator`` on the CPU, seeded per workload):
   padding   one vector p (drawn like a row) per batch; the last ceil(pad_frac*L) positions of
             every sequence are bit-identical copies of p
   dY        N(0, 0.1^2)  (variance 1e-2)
+  Pt        for the random-projection baseline (Sec. 4.6): r directions, entries N(0, 1/r), so that E[P P^T] = I
 Values are drawn in float32 and then rounded once to the workload's element type;
 the rounded values are what every consumer sees.
 """
@@ -123,3 +124,16 @@ def generate_dy(w: Workload) -> torch.Tensor:
 def generate(w: Workload):
     """(X, dY) as contiguous CPU tensors of the workload's element type."""
     return generate_x(w), generate_dy(w)
+
+
+def sketch_directions(w: Workload, r: int) -> torch.Tensor:
+    """Pt (r x n): the transpose of the random projection P of the sketch baseline, entries N(0, 1/r)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed + 104729)
+    return (torch.randn(r, w.n, generator=g) / math.sqrt(r)).to(w.torch_dtype).contiguous()
+
+
+def matched_sketch_width(w: Workload) -> int:
+    """Sketch width whose b r stored numbers are at least the k n + 2 b that PAMM keeps, as a whole 16-byte row."""
+    r = -(-(w.k * w.n + 2 * w.b) // w.b)
+    return max(8, -(-r // 8) * 8)

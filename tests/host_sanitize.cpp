@@ -117,6 +117,31 @@ int main() {
     REQUIRE(check_grad_args(A, A, A, A, 64, 64, 4, 64, PAMM_BF16, PAMM_F32, PAMM_DW_N_BY_M, A, nullptr, plenty, &gp) == PAMM_ERR_WORKSPACE);
     REQUIRE(check_grad_args(A, A, A, A, 64, 64, 4, 64, PAMM_BF16, PAMM_F32, PAMM_DW_N_BY_M, A, A, 1024, &gp) == PAMM_ERR_WORKSPACE);
 
+    // ---- the sketch baseline: planner over ordinary and extreme sizes, argument checks
+    for (int64_t b : {int64_t(128), int64_t(700), int64_t(65536), big})
+        for (int64_t r : {int64_t(8), int64_t(24), int64_t(72), int64_t(128)})
+            for (int64_t m : {int64_t(8), int64_t(6144), big}) {
+                pamm::SketchGradPlan sp;
+                REQUIRE(pamm::plan_sketch_grad(b, 2048, r, m, PAMM_BF16, &sp) == PAMM_OK);
+                REQUIRE(sp.total == pamm_sketch_grad_workspace(b, 2048, r, m, PAMM_BF16) && sp.total > 0);
+                REQUIRE(sp.chunk_rows % 32 == 0 && sp.chunks * sp.chunk_rows >= b && (sp.chunks - 1) * sp.chunk_rows < b);
+                REQUIRE(int64_t(sp.col_groups) * 512 >= m && sp.nr * 32 >= r && sp.g.kpad >= r && sp.g.off_bt < sp.total);
+            }
+    pamm::SketchGradPlan sp;
+    REQUIRE(check_sketch_args(A, A, 64, 64, 8, PAMM_BF16, A) == PAMM_OK);
+    REQUIRE(check_sketch_args(A, A, 64, 64, 4, PAMM_F32, A) == PAMM_OK);
+    REQUIRE(check_sketch_args(A, nullptr, 64, 64, 8, PAMM_BF16, A) == PAMM_ERR_INVALID_ARG);
+    REQUIRE(check_sketch_args(A, A, 64, 64, 8, PAMM_BF16, odd) == PAMM_ERR_INVALID_ARG);
+    REQUIRE(check_sketch_args(A, A, 4, 64, 8, PAMM_BF16, A) == PAMM_ERR_INVALID_ARG);
+    REQUIRE(check_sketch_args(A, A, 64, 64, 12, PAMM_BF16, A) == PAMM_ERR_UNSUPPORTED);
+    REQUIRE(check_sketch_args(A, A, 256, 64, 136, PAMM_BF16, A) == PAMM_ERR_UNSUPPORTED);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_BF16, A, A, plenty, &sp) == PAMM_OK);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_F32, A, A, plenty, &sp) == PAMM_ERR_UNSUPPORTED);
+    REQUIRE(check_sketch_grad_args(A, A, nullptr, 64, 64, 8, 64, PAMM_BF16, A, A, plenty, &sp) == PAMM_ERR_INVALID_ARG);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 12, PAMM_BF16, A, A, plenty, &sp) == PAMM_ERR_UNSUPPORTED);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_BF16, A, A, 256, &sp) == PAMM_ERR_WORKSPACE);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_BF16, A, nullptr, plenty, &sp) == PAMM_ERR_WORKSPACE);
+
     double keep = 0.0;
     REQUIRE(keep_of(0.5f, &keep) == PAMM_OK && keep == 0.75);
     REQUIRE(keep_of(1.0f, &keep) == PAMM_OK && keep < 0.0);

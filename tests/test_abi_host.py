@@ -209,6 +209,39 @@ def test_grad_out_argument_checks(pamm):
     assert _grad_out(P, dt=0, n=4, m=4, out_dt=1, layout=0, ws=None) == P.PAMM_ERR_WORKSPACE
 
 
+def _sketch(pamm, X=A, Pt=A, b=64, n=64, r=8, dt=1, S=A):
+    return pamm.lib.pamm_sketch(X, Pt, b, n, r, dt, S, None)
+
+
+def _sketch_grad(pamm, Pt=A, S=A, dY=A, b=64, n=64, r=8, m=64, dt=1, dW=A, ws=A, ws_bytes=BIG):
+    return pamm.lib.pamm_sketch_grad(Pt, S, dY, b, n, r, m, dt, dW, ws, ws_bytes, None)
+
+
+def test_sketch_argument_checks(pamm):
+    P = pamm
+    for kw in ("X", "Pt", "S"):
+        assert _sketch(P, **{kw: None}) == P.PAMM_ERR_INVALID_ARG
+        assert _sketch(P, **{kw: A + 4}) == P.PAMM_ERR_INVALID_ARG
+    assert _sketch(P, r=0) == P.PAMM_ERR_INVALID_ARG
+    assert _sketch(P, b=4, r=8) == P.PAMM_ERR_INVALID_ARG             # more directions than rows
+    assert _sketch(P, r=12) == P.PAMM_ERR_UNSUPPORTED                 # rows of S not 16-byte aligned
+    assert _sketch(P, b=256, r=136) == P.PAMM_ERR_UNSUPPORTED         # wider than the widest sketch
+    assert _sketch(P, n=60) == P.PAMM_ERR_UNSUPPORTED
+    assert _sketch(P, dt=5) == P.PAMM_ERR_UNSUPPORTED
+    for kw in ("Pt", "S", "dY", "dW"):
+        assert _sketch_grad(P, **{kw: None}) == P.PAMM_ERR_INVALID_ARG
+    assert _sketch_grad(P, dt=0) == P.PAMM_ERR_UNSUPPORTED            # fp32: not built
+    assert _sketch_grad(P, m=12) == P.PAMM_ERR_UNSUPPORTED
+    assert _sketch_grad(P, m=0) == P.PAMM_ERR_INVALID_ARG
+    assert _sketch_grad(P, ws=None) == P.PAMM_ERR_WORKSPACE
+    assert _sketch_grad(P, ws_bytes=1024) == P.PAMM_ERR_WORKSPACE
+    # the workspace holds one partial row of G per sketch column and chunk, and both operands of the last product
+    need = P.sketch_grad_workspace(65536, 2048, 8, 6144, P.PAMM_BF16)
+    assert need >= 8 * 6144 * 4 * 2 and need < (64 << 20)
+    assert P.sketch_grad_workspace(65536, 2048, 8, 6144, P.PAMM_F32) == 0
+    assert P.sketch_grad_workspace(65536, 2048, 136, 6144, P.PAMM_BF16) == 0
+
+
 def test_binding_refuses_cpu_tensors(pamm):
     import torch
 

@@ -1,0 +1,147 @@
+"""GPU parity of the random-projection baseline (Sec. 4.6: the layer keeps S = X P and estimates the weight gradient as
+P S^T dY) against the fp64 oracle, element by element.
+
+Bars (u = 2^-8, the unit roundoff of bf16; abs(.) marks the same expression evaluated on absolute values, the
+scale that rounding errors are relative to):
+  S     bf16: u |S| + 6e-6 abs(S)   one rounding of the stored sketch on top of an fp32 sum of exact products
+        f32 : 1e-5 abs(S)            fp32 products and sums
+  dW    (u + 5e-6) abs(dW)          G = S^T dY summed in fp32, rounded once to bf16, times Pt^T in fp32: the bar of
+                                    pamm_grad's bf16 path, whose last two steps these are
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_02939_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+U16 = 2.0 ** -8
+
+
+@pytest.fixture(scope="module")
+def pamm():
+    assert torch.cuda.is_available(), "GPU tests need the MI355X"
+    from paper_2506_02939_amd import pamm as p
+
+    return p
+
+
+def _check_sketch(oracle, X, Pt, S_gpu):
+    S = oracle.sketch(X, Pt)
+    S_abs = oracle.sketch(X.abs(), Pt.abs())
+    got = S_gpu.float().cpu().numpy().astype(np.float64)
+    if X.dtype == torch.bfloat16:
+        bar = (U16 + 1e-6) * np.abs(S) + 6e-6 * S_abs
+    else:
+        bar = 1e-5 * S_abs
+    err = np.abs(got - S)
+    assert np.all(err <= bar + 1e-30), f"S off by {np.max(err / np.maximum(bar, 1e-300))} bars"
+
+
+def _check_grad(oracle, Pt, S, dY, dW_gpu):
+    _, O = oracle.sketch_grad(Pt, S, dY)
+    _, O_abs = oracle.sketch_grad(Pt.abs(), S.abs(), dY.abs())
+    err = np.abs(dW_gpu.cpu().numpy().astype(np.float64) - O)
+    assert np.all(err <= (U16 + 5e-6) * O_abs + 1e-30), f"dW off by {np.max(err / np.maximum(O_abs, 1e-300))}"
+    assert np.linalg.norm(err) <= U16 * np.linalg.norm(O)
+
+
+CASES = [
+    # name, base workload, overrides, sketch width
+    ("r8_ragged", "llama60m", dict(seqs=5, seq_len=77, n=72, m=520, k=7, centres=16), 8),
+    ("r24_two_column_groups", "llama60m", dict(seqs=3, seq_len=333, n=200, m=1032, k=7, centres=16), 24),
+    ("r40", "llama350m", dict(seqs=4, seq_len=300, n=264, m=776, k=7, centres=32), 40),
+    ("r72", "llama350m", dict(seqs=2, seq_len=450, n=136, m=1544, k=7, centres=32), 72),
+    ("r128_many_chunks", "llama1b", dict(seqs=9, seq_len=1000, n=256, m=2056, k=7, centres=64), 128),
+    ("r16_many_chunks", "llama1b", dict(seqs=16, seq_len=1021, n=512, m=4608, k=7, centres=64), 16),
+]
+
+
+@pytest.mark.parametrize("name,base,over,r", CASES, ids=[c[0] for c in CASES])
+def test_sketch_and_its_gradient_estimate(pamm, oracle, name, base, over, r):
+    w = workloads.scaled(workloads.WORKLOADS[base], **over)
+    X, dY = workloads.generate(w)
+    Pt = workloads.sketch_directions(w, r)
+    print(f"[case] sketch {name} b={w.b} n={w.n} m={w.m} r={r}", flush=True)
+    S_gpu = pamm.sketch(X.cuda(), Pt.cuda())
+    torch.cuda.synchronize()
+    assert S_gpu.shape == (w.b, r) and S_gpu.dtype == X.dtype
+    _check_sketch(oracle, X, Pt, S_gpu)
+    # the estimate from the GPU's own sketch, and from the oracle's (rounded to the element type the layer keeps)
+    dW = pamm.sketch_grad(Pt.cuda(), S_gpu, dY.cuda())
+    dW2 = pamm.sketch_grad(Pt.cuda(), S_gpu, dY.cuda())
+    torch.cuda.synchronize()
+    assert dW.shape == (w.n, w.m) and dW.dtype == torch.float32
+    assert torch.equal(dW, dW2), "two calls on the same inputs differ"
+    _check_grad(oracle, Pt, S_gpu.cpu(), dY, dW)
+    S_or = torch.from_numpy(oracle.sketch(X, Pt)).to(X.dtype)
+    dW3 = pamm.sketch_grad(Pt.cuda(), S_or.cuda(), dY.cuda())
+    torch.cuda.synchronize()
+    _check_grad(oracle, Pt, S_or, dY, dW3)
+
+
+@pytest.mark.parametrize("n,r", [(256, 8), (100, 20), (516, 128)])
+def test_sketch_of_fp32_inputs(pamm, oracle, n, r):
+    w = workloads.scaled(workloads.WORKLOADS["tiny"], seqs=3, seq_len=171, n=n, m=64, k=5, centres=12)
+    X, _ = workloads.generate(w)
+    Pt = workloads.sketch_directions(w, r)
+    S_gpu = pamm.sketch(X.cuda(), Pt.cuda())
+    torch.cuda.synchronize()
+    _check_sketch(oracle, X, Pt, S_gpu)
+
+
+def test_identity_directions_reproduce_the_input_and_the_exact_product(pamm, oracle):
+    """r = n = 128 with P = I: S is X bit for bit, and the estimate is X^T dY at the bar."""
+    w = workloads.scaled(workloads.WORKLOADS["llama60m"], seqs=3, seq_len=250, n=128, m=520, k=7, centres=16)
+    X, dY = workloads.generate(w)
+    Pt = torch.eye(128, dtype=X.dtype)
+    S = pamm.sketch(X.cuda(), Pt.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(S.cpu(), X)
+    dW = pamm.sketch_grad(Pt.cuda(), S, dY.cuda())
+    torch.cuda.synchronize()
+    exact = oracle.to_f64(X).T @ oracle.to_f64(dY)
+    exact_abs = np.abs(oracle.to_f64(X)).T @ np.abs(oracle.to_f64(dY))
+    assert np.all(np.abs(dW.cpu().numpy().astype(np.float64) - exact) <= (U16 + 5e-6) * exact_abs)
+
+
+def test_memory_matched_sketch_at_the_headline_shape(pamm, oracle):
+    """The sketch as wide as PAMM's compression is big (b r >= k n + 2 b) at the 1B-shaped layer, full size, in the
+    launch configuration the benchmark times; every element against the oracle."""
+    w = workloads.WORKLOADS["llama1b"]
+    r = workloads.matched_sketch_width(w)
+    assert r == 8
+    X, dY = workloads.generate(w)
+    Pt = workloads.sketch_directions(w, r)
+    S = pamm.sketch(X.cuda(), Pt.cuda())
+    dW = pamm.sketch_grad(Pt.cuda(), S, dY.cuda())
+    torch.cuda.synchronize()
+    print("[case] sketch llama1b r=8: oracle", flush=True)
+    _check_sketch(oracle, X, Pt, S)
+    _check_grad(oracle, Pt, S.cpu(), dY, dW)
+
+
+def test_argument_errors(pamm):
+    from paper_2506_02939_amd.pamm import PammError, PAMM_ERR_UNSUPPORTED, PAMM_ERR_WORKSPACE, PAMM_ERR_INVALID_ARG, PAMM_BF16, PAMM_F32
+
+    X = torch.zeros(256, 64, dtype=torch.bfloat16, device="cuda")
+    dY = torch.zeros(256, 128, dtype=torch.bfloat16, device="cuda")
+    for r in (12, 136):
+        with pytest.raises(PammError) as e:
+            pamm.sketch(X, torch.zeros(r, 64, dtype=torch.bfloat16, device="cuda"))
+        assert e.value.status == PAMM_ERR_UNSUPPORTED
+    Pt = torch.zeros(8, 64, dtype=torch.bfloat16, device="cuda")
+    S = pamm.sketch(X, Pt)
+    with pytest.raises(PammError) as e:
+        pamm.sketch_grad(Pt, S, dY, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == PAMM_ERR_WORKSPACE
+    with pytest.raises(PammError) as e:
+        pamm.sketch_grad(Pt.float(), S.float(), dY.float())
+    assert e.value.status == PAMM_ERR_UNSUPPORTED
+    assert pamm.sketch_grad_workspace(256, 64, 8, 128, PAMM_F32) == 0
+    assert pamm.sketch_grad_workspace(256, 64, 8, 128, PAMM_BF16) > 0
+    with pytest.raises(PammError) as e:          # more directions than rows
+        pamm.sketch(X[:4], Pt)
+    assert e.value.status == PAMM_ERR_INVALID_ARG
+    torch.cuda.synchronize()
