@@ -10,6 +10,9 @@ events on the launch stream (the library's own per-kernel event hooks) over a se
 HBM peak and, where the kernel is a matrix product that outruns its bytes, against the bf16 matrix peak.  `configs`
 carries every workload of the benchmark's configuration list (median step time, per-kernel durations and roofline
 fractions, counter traffic from profiles/), each timed like the headline over `--config-steps` steps.
+`sketch` times the random-projection baseline of Sec. 4.6 (pamm_sketch + pamm_sketch_grad) on the headline workload at
+the width that stores as much as PAMM's compression does, the same way, and gives both estimates' distance from the exact
+product X^T dY (the shape of the paper's ablation, on synthetic data).
 `cpu_baseline` is the fp64 oracle timed on this machine's host cores on the headline batch.  `exact_gemm` is the
 plain X^T dY product (vendor BLAS through torch.matmul) on the same GPU, for scale only.
 """
@@ -148,6 +151,67 @@ def time_workload(torch, pamm, workloads, name, steps, warmup, nsets, eps=None, 
     return rec, dict(w=w, X_cpu=X_cpu, dY_cpu=dY_cpu, X=Xs[0], dY=dYs[0], per_kernel_us=per_kernel_us)
 
 
+def time_sketch(torch, pamm, workloads, name, steps, warmup, nsets):
+    """The random-projection baseline on one workload: K timed steps of sketch + sketch_grad at the memory-matched width,
+    per-kernel durations, and the relative error of both estimates of X^T dY."""
+    w = workloads.WORKLOADS[name]
+    if w.dtype != "bf16":
+        return None
+    r = workloads.matched_sketch_width(w)
+    X_cpu, dY_cpu = workloads.generate(w)
+    Xs = [X_cpu.cuda() for _ in range(nsets)]
+    dYs = [dY_cpu.cuda() for _ in range(nsets)]
+    Pt = workloads.sketch_directions(w, r).cuda()
+    b, n, m, k = w.b, w.n, w.m, w.k
+    S = torch.empty(b, r, dtype=Xs[0].dtype, device="cuda")
+    dW = torch.empty(n, m, dtype=torch.float32, device="cuda")
+    ws = torch.empty(pamm.sketch_grad_workspace(b, n, r, m, pamm.PAMM_BF16), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        pamm.sketch(Xs[i % nsets], Pt, out=S)
+        pamm.sketch_grad(Pt, S, dYs[i % nsets], out=dW, ws=ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    pamm.profile_begin()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    prof = pamm.profile_end()
+    per_kernel_us = {kname: 1e3 * ms / cnt for kname, (ms, cnt) in prof.items()}
+    alg = {"k_sketch": b * n * 2 + b * r * 2, "k_sketch_contract": b * m * 2 + b * r * 2 + r * m * 4,
+           "k_ctb": n * m * 4 + r * n * 2 + r * m * 4}
+    kernels = {}
+    for kname, us in per_kernel_us.items():
+        ent = {"avg_us": round(us, 2)}
+        if kname in alg:
+            gbs = alg[kname] / (us * 1e-6) / 1e9
+            ent.update(algorithmic_bytes=alg[kname], algorithmic_GBps=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4),
+                       bound="hbm", traffic=read_traffic(w.name, kname))
+        kernels[kname] = ent
+
+    # how far both estimates are from the exact product, in relative Frobenius norm (fp32 product of the same inputs)
+    exact = torch.matmul(Xs[0].float().t(), dYs[0].float())
+    step(0)
+    err_sketch = float((dW - exact).norm() / exact.norm())
+    c = pamm.compress(Xs[0], k, seed=0)
+    err_pamm = float((pamm.grad(c.C, c.f, c.alpha, dYs[0]) - exact).norm() / exact.norm())
+    torch.cuda.synchronize()
+    return {
+        "workload": w.name, "r": r, "stored_numbers": {"sketch": b * r, "pamm": k * n + 2 * b},
+        "ms_per_step": round(ms_per_step, 4), "tokens_per_s": round(b / (ms_per_step * 1e-3), 1),
+        "launches_per_step": round(sum(cnt for _, cnt in prof.values()) / steps, 2), "kernels": kernels,
+        "rel_error_vs_exact": {"sketch": round(err_sketch, 4), "pamm": round(err_pamm, 4)},
+        "what": "S = X P, dW = P S^T dY with P Gaussian (Sec. 4.6), same inputs, same rotation of input copies as the headline",
+    }
+
+
 ALL_WORKLOADS = ["tiny", "llama60m", "llama350m", "llama1b", "llama7b_k32", "llama7b_k256", "llama7b_k1024"]
 
 
@@ -170,6 +234,7 @@ def main() -> int:
                          "vendor BLAS) against the same layer with the exact weight gradient; adds a \"layer\" object")
     ap.add_argument("--no-configs", action="store_true", help="time the headline workload only (no \"configs\" array)")
     ap.add_argument("--config-steps", type=int, default=100, help="timed steps for each entry of the \"configs\" array")
+    ap.add_argument("--no-sketch", action="store_true", help="do not time the random-projection baseline (no \"sketch\" object)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact-gemm", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -242,6 +307,12 @@ def main() -> int:
         gms = (time.perf_counter() - g0) * 1e3 / reps_g
         result["exact_gemm"] = {"ms": round(gms, 4), "tokens_per_s": round(b / (gms * 1e-3), 1),
                                 "TFLOPs": round(2.0 * b * n * m / (gms * 1e-3) / 1e12, 1), "kind": "torch.matmul(X^T, dY), same GPU"}
+
+    if not args.no_sketch:
+        torch.cuda.empty_cache()
+        sk = time_sketch(torch, pamm, workloads, w.name, min(args.steps, args.config_steps), min(args.warmup, 10), nsets)
+        if sk is not None:
+            result["sketch"] = sk
 
     if args.layer:
         from paper_2506_02939_amd import linear

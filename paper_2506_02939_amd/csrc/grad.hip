@@ -1028,96 +1028,85 @@ __global__ __launch_bounds__(256, FQ == 2 ? 2 : 1) void k_ctb_big(const u32x4_t*
 // every one of the r sketch columns, so it is a dense product with the tokens as contraction index and runs on the
 // matrix cores while dY streams once from HBM.
 //
-// k_sketch_contract.  Workgroup = 4 waves, one chunk of tokens x 512 columns of dY; wave w owns columns [128 w, +128):
-// NR x 4 accumulator fragments (NR = ceil(r / 32)).  The tokens are walked in stages of 32; a stage is 32 rows x 64
-// chunks of dY (32 KiB) and 32 rows x 4 NR chunks of S, in a ring of LDS buffers filled by loads that go from global
-// memory straight into LDS (pamm_tile256.h describes the technique: a load instruction of dY takes one whole row of the
-// stage, 1 KiB contiguous; chunk c of stage row t is kept at c ^ 4 (t % 4)), and both MFMA operands come out of
-// transposing LDS reads: both matrices have the contraction index across their rows.  S is tiny next to dY; the lanes
-// of its loads that fall past the end of the tokens or of the sketch's columns fetch a chunk of zeros instead, which
-// also makes the rows of dY past the end (clamped onto the last row) count for nothing.
-// Output: one partial row of G per sketch column and chunk, partial[(j chunks + chunk) m + c], which the kernels of
-// the small product then sum like the pieces of a generator.
-__global__ void k_sketch_init(int r, int chunks, int32_t* __restrict__ sbase, int32_t* __restrict__ snum, u32x4_t* __restrict__ zero) {
-    const int j = threadIdx.x;
-    if (j < r) { sbase[j] = j * chunks; snum[j] = chunks; }
-    if (j == 0) *zero = u32x4_t{0u, 0u, 0u, 0u};
-}
-
+// k_sketch_contract.  One wave per (chunk of tokens, 128 columns of dY): NR x 4 accumulator fragments (NR = ceil(r / 32)).
+// The four waves of a workgroup sit side by side along the row but never wait for each other: every wave runs its own
+// pipeline through its own part of the LDS, so a load that comes back late from HBM holds up one wave, not four (with a
+// workgroup barrier per stage the kernel ran at two thirds of this rate).  The tokens are walked in stages of 16 (one
+// MFMA step); a wave's stage is 16 rows x 16 chunks of dY (4 KiB) and 16 rows x 4 NR chunks of S, in a ring of LDS
+// buffers filled by loads that go from global memory straight into LDS (pamm_tile256.h describes the technique: a load
+// instruction of dY takes four rows of the stage, 256 contiguous bytes of each; chunk c of stage row t is kept at
+// c ^ 4 (t % 4)), and both MFMA operands come out of transposing LDS reads: both matrices have the contraction index
+// across their rows.  S is tiny next to dY; the lanes of its loads that fall past the end of the tokens or of the
+// sketch's columns fetch a chunk of zeros instead, which also makes the rows of dY past the end (clamped onto the last
+// row) count for nothing.  Workgroup 0 leaves the table of pieces for the kernels of the small product.
+// Output: one partial row of G per sketch column and chunk, partial[(j chunks + chunk) m + c], which those kernels
+// then sum like the pieces of a generator.
 template <int NR>
 struct SketchLds {
-    static constexpr int kNB = NR <= 2 ? 4 : 3;                 // stage buffers that fit the LDS
-    static constexpr int kSL = (NR + 1) / 2;                    // load instructions of S per wave and stage
-    static constexpr int kStageY = 2048;                        // chunks: 32 rows x 512 columns of bf16
-    static constexpr int kStageS = 256 * kSL;                   // 32 rows x 4 NR chunks, rounded up to whole load instructions
-    static constexpr int kStage = kStageY + kStageS;
-    static_assert(kNB * kStage * 16 <= 152 * 1024, "the stage ring does not fit the LDS of a compute unit");
+    static constexpr int kNB = NR == 1 ? 7 : (NR == 2 ? 6 : (NR == 3 ? 5 : 4));      // stage buffers that fit the LDS
+    static constexpr int kStageY = 256;                         // chunks: 16 rows x 128 columns of bf16
+    static constexpr int kStageS = 64 * NR;                     // 16 rows x 4 NR chunks
+    static constexpr int kStage = kStageY + kStageS;            // of one wave
+    static_assert(4 * kNB * kStage * 16 <= 152 * 1024, "the stage rings do not fit the LDS of a compute unit");
 };
 
+// The wave's walk.  (A function of its own with __restrict__ sources on purpose: that is what lets the compiler keep
+// the LDS reads apart from the loads into LDS still in flight; in the kernel's own body it makes every LDS read wait for
+// ALL outstanding loads, which empties the pipeline at every stage.  The waits that matter are the counted ones below.)
 template <int NR>
-__global__ __launch_bounds__(256) void k_sketch_contract(const u32x4_t* __restrict__ S, const u32x4_t* __restrict__ dY,
-                                                         const u32x4_t* __restrict__ zero, int b, int rch, int mch, int m,
-                                                         int col_groups, int chunk_rows, int chunks, int r,
-                                                         float* __restrict__ partial) {
+__device__ __forceinline__ void sketch_contract_wave(u32x4_t* __restrict__ lds, const u32x4_t* __restrict__ S,
+                                                     const u32x4_t* __restrict__ dY, const u32x4_t* __restrict__ zero, int b, int rch,
+                                                     int mch, int m, int chunk, int chunks, int t0, int nst, int c0, int r,
+                                                     float* __restrict__ partial) {
     typedef SketchLds<NR> L;
     typedef __attribute__((ext_vector_type(4))) short s16x4_t;
     typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
-    constexpr int NB = L::kNB, SL = L::kSL, NLW = 8 + SL;       // NLW: loads per wave and stage
-    __shared__ u32x4_t lds[NB * L::kStage];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, rr = lane & 31, g = lane >> 5;
-    const int chunk = blockIdx.x / col_groups, cg = blockIdx.x % col_groups;
-    const int t0 = chunk * chunk_rows, t1 = min(b, t0 + chunk_rows);
-    const int nst = (t1 - t0 + 31) / 32;
+    constexpr int NB = L::kNB, NLW = 4 + NR;                     // NLW: loads per stage
+    const int lane = threadIdx.x & 63, rr = lane & 31, g = lane >> 5;
 
-    // this lane's part of the loads of a stage: for dY the column chunk (the row is the instruction's), for S row and chunk
-    int ycol[8];
+    // this lane's part of the loads of a stage: for dY row and column chunk, for S row and chunk
+    const int yrow = lane >> 4;                                  // + 4 i for load i
+    const int ycol = min(c0 / 8 + ((lane & 15) ^ ((yrow & 3) << 2)), mch - 1);
+    int srow[NR], scol[NR];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int krow = 8 * wave + i;
-        ycol[i] = min(cg * 64 + (lane ^ ((krow & 3) << 2)), mch - 1);
-    }
-    int srow[SL], scol[SL];
-#pragma unroll
-    for (int i = 0; i < SL; ++i) {
-        const int q = 64 * (SL * wave + i) + lane;               // chunk of the S stage, row-major with 4 NR chunks per row
+    for (int i = 0; i < NR; ++i) {
+        const int q = 64 * i + lane;                             // chunk of the S stage, row-major with 4 NR chunks per row
         srow[i] = q / (4 * NR);
-        scol[i] = (q < 128 * NR && q % (4 * NR) < rch) ? q % (4 * NR) : -1;
+        scol[i] = (q % (4 * NR) < rch) ? q % (4 * NR) : -1;
     }
     auto issue = [&](int stage, int buf) {
         stage = min(stage, nst - 1);                             // past the end: the last stage once more, into a free buffer
-        const int tbase = t0 + 32 * stage;
+        const int tbase = t0 + 16 * stage;
         u32x4_t* const dst = lds + buf * L::kStage;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int tok = min(tbase + 8 * wave + i, b - 1);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dY + size_t(tok) * mch + ycol[i]),
-                                             (__attribute__((address_space(3))) void*)(dst + (8 * wave + i) * 64), 16, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+            const int tok = min(tbase + 4 * i + yrow, b - 1);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dY + size_t(tok) * mch + ycol),
+                                             (__attribute__((address_space(3))) void*)(dst + i * 64), 16, 0, 2 /* nt: read once */);
         }
 #pragma unroll
-        for (int i = 0; i < SL; ++i) {
+        for (int i = 0; i < NR; ++i) {
             const int tok = tbase + srow[i];
             const u32x4_t* src = (scol[i] >= 0 && tok < b) ? S + size_t(tok) * rch + scol[i] : zero;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(dst + L::kStageY + 64 * (SL * wave + i)), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(dst + L::kStageY + 64 * i), 16, 0, 0);
         }
     };
-    // fragment addresses inside a stage buffer in 16-bit elements, for the two MFMA steps of a stage and the two
-    // transposing reads of a fragment (this lane addresses stage row t, columns col .. col + 3 of a 4 x 16 block)
-    int off_y[2][2], off_s[2][2], frag_y[4];
+    // fragment addresses inside a stage buffer in 16-bit elements, for the two transposing reads of a fragment (this
+    // lane addresses stage row t, columns col .. col + 3 of a 4 x 16 block)
+    int off_y[2], off_s[2], frag_y[4];
     {
         const int G = lane >> 4, p = lane & 15, kk = (p >> 2) & 3;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int h = 0; h < 2; ++h) {
+            const int t = 8 * (G >> 1) + 4 * h + (p >> 2);       // t % 4 == kk
+            const int col = 16 * (G & 1) + 4 * (p & 3);
+            off_y[h] = t * 128 + col;
+            off_s[h] = L::kStageY * 8 + t * (32 * NR) + col;
+        }
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int t = 16 * u + 8 * (G >> 1) + 4 * h + (p >> 2);      // t % 4 == kk
-                const int col = 16 * (G & 1) + 4 * (p & 3);
-                off_y[u][h] = t * 512 + col;
-                off_s[u][h] = L::kStageY * 8 + t * (32 * NR) + col;
-            }
-#pragma unroll
-        for (int f = 0; f < 4; ++f) frag_y[f] = 8 * ((16 * wave + 4 * f) ^ (kk << 2));
+        for (int f = 0; f < 4; ++f) frag_y[f] = 8 * ((4 * f) ^ (kk << 2));
     }
     auto read_frag = [&](const short* base, int o0, int o1) {
         const u32x2_t lo = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(base + o0)));
@@ -1132,47 +1121,65 @@ __global__ __launch_bounds__(256) void k_sketch_contract(const u32x4_t* __restri
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][f][i] = 0.f;
 
+    // Nothing here crosses waves: a wave's LDS reads follow its own loads (counted wait), and its loads into a buffer
+    // follow its own reads of that buffer, whose results the MFMAs of the previous round have consumed.
     for (int d = 0; d < NB - 1; ++d) issue(d, d);
-    wait_vmcnt<NLW * (NB - 2)>();
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
     int cur = 0, load_buf = NB - 1;
     for (int s = 0; s < nst; ++s) {
-        issue(s + NB - 1, load_buf);              // into the buffer consumed before the last barrier
+        wait_vmcnt<NLW * (NB - 2)>();             // stage s has landed (the younger ones stay in flight)
+        __builtin_amdgcn_sched_barrier(0);
         const short* base = reinterpret_cast<const short*>(lds + cur * L::kStage);
+        u32x4_t fs[NR], fy[4];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            u32x4_t fs[NR], fy[4];
+        for (int a = 0; a < NR; ++a) fs[a] = read_frag(base, off_s[0] + 32 * a, off_s[1] + 32 * a);
 #pragma unroll
-            for (int a = 0; a < NR; ++a) fs[a] = read_frag(base, off_s[u][0] + 32 * a, off_s[u][1] + 32 * a);
+        for (int f = 0; f < 4; ++f) fy[f] = read_frag(base, off_y[0] + frag_y[f], off_y[1] + frag_y[f]);
 #pragma unroll
-            for (int f = 0; f < 4; ++f) fy[f] = read_frag(base, off_y[u][0] + frag_y[f], off_y[u][1] + frag_y[f]);
+        for (int a = 0; a < NR; ++a)
 #pragma unroll
-            for (int a = 0; a < NR; ++a)
-#pragma unroll
-                for (int f = 0; f < 4; ++f) Bf16::mma(fs[a], fy[f], acc[a][f]);
-        }
+            for (int f = 0; f < 4; ++f) Bf16::mma(fs[a], fy[f], acc[a][f]);
         __builtin_amdgcn_sched_barrier(0);
-        wait_vmcnt<NLW * (NB - 2)>();             // stage s + 1 has landed (the younger ones stay in flight)
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
+        issue(s + NB - 1, load_buf);              // into the buffer read one stage ago
         cur = cur + 1 == NB ? 0 : cur + 1;
         load_buf = load_buf + 1 == NB ? 0 : load_buf + 1;
     }
     wait_vmcnt<0>();
 
-    // register i of acc[a][f]: sketch column 32 a + 8 (i / 4) + 4 g + i % 4, column 128 wave + 32 f + rr of the group
+    // register i of acc[a][f]: sketch column 32 a + 8 (i / 4) + 4 g + i % 4, column c0 + 32 f + rr
 #pragma unroll
     for (int a = 0; a < NR; ++a)
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
-            const int c = cg * 512 + 128 * wave + 32 * f + rr;
+            const int c = c0 + 32 * f + rr;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int j = 32 * a + 8 * (i >> 2) + 4 * g + (i & 3);
                 if (j < r && c < m) partial[(size_t(j) * chunks + chunk) * m + c] = acc[a][f][i];
             }
         }
+}
+
+template <int NR>
+__global__ __launch_bounds__(256) void k_sketch_contract(const u32x4_t* __restrict__ S, const u32x4_t* __restrict__ dY,
+                                                         u32x4_t* __restrict__ zero, int b, int rch, int mch, int m,
+                                                         int col_groups, int chunk_rows, int chunks, int r,
+                                                         int32_t* __restrict__ sbase, int32_t* __restrict__ snum,
+                                                         float* __restrict__ partial) {
+    typedef SketchLds<NR> L;
+    __shared__ u32x4_t lds_all[4 * L::kNB * L::kStage];
+    const int wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x / col_groups, cg = blockIdx.x % col_groups;
+    const int t0 = chunk * chunk_rows, t1 = min(b, t0 + chunk_rows);
+    // The chunk of zeros: every workgroup writes the same 16 bytes and reads back only what it wrote itself, so the
+    // workgroup barrier is all the ordering it takes (a device-wide fence here cost a fifth of the kernel's time).
+    // From workgroup 0, the table of pieces: sketch column j owns the partial rows j chunks .. j chunks + chunks - 1.
+    if (threadIdx.x == 0) *zero = u32x4_t{0u, 0u, 0u, 0u};
+    if (blockIdx.x == 0 && threadIdx.x < r) { sbase[threadIdx.x] = int(threadIdx.x) * chunks; snum[threadIdx.x] = chunks; }
+    __syncthreads();
+    const int c0 = cg * 512 + wave * 128;                        // this wave's first column
+    if (c0 >= m) return;                                         // this wave has no columns (uniform per wave)
+    sketch_contract_wave<NR>(lds_all + wave * (L::kNB * L::kStage), S, dY, zero, b, rch, mch, m, chunk, chunks, t0, (t1 - t0 + 15) / 16,
+                             c0, r, partial);
 }
 
 // ------------------------------------------------------------------------------------------------ host side
@@ -1405,11 +1412,11 @@ extern "C" pamm_status pamm_sketch_grad(const void* Pt, const void* S, const voi
     u32x4_t* zero = reinterpret_cast<u32x4_t*>((char*)ws + pl.off_zero);
     {
         ScopedSpan span(kSketchContract, s);
-        hipLaunchKernelGGL(k_sketch_init, dim3(1), dim3(128), 0, s, int(r), int(pl.chunks), g.sbase, g.snum, zero);
         const dim3 grid((unsigned)(pl.chunks * pl.col_groups));
 #define PAMM_LAUNCH_SKETCH_CONTRACT(NRV)                                                                                             \
-    hipLaunchKernelGGL(k_sketch_contract<NRV>, grid, dim3(256), 0, s, (const u32x4_t*)S, (const u32x4_t*)dY, (const u32x4_t*)zero, \
-                       int(b), int(r / 8), int(m / 8), int(m), pl.col_groups, int(pl.chunk_rows), int(pl.chunks), int(r), g.partial)
+    hipLaunchKernelGGL(k_sketch_contract<NRV>, grid, dim3(256), 0, s, (const u32x4_t*)S, (const u32x4_t*)dY, zero, int(b),       \
+                       int(r / 8), int(m / 8), int(m), pl.col_groups, int(pl.chunk_rows), int(pl.chunks), int(r), g.sbase, g.snum, \
+                       g.partial)
         if (pl.nr == 1) PAMM_LAUNCH_SKETCH_CONTRACT(1);
         else if (pl.nr == 2) PAMM_LAUNCH_SKETCH_CONTRACT(2);
         else if (pl.nr == 3) PAMM_LAUNCH_SKETCH_CONTRACT(3);

@@ -234,8 +234,10 @@ inline pamm_status plan_sketch_grad(int64_t b, int64_t n, int64_t r, int64_t m, 
     if (m % 8 != 0) return PAMM_ERR_UNSUPPORTED;
     p->nr = int((r + 31) / 32);
     p->col_groups = int((m + 511) / 512);
-    // two workgroups per compute unit in all (each streams its chunk of 512 columns; the LDS ring admits one at a time)
-    const int64_t want = (2 * kNumCU + p->col_groups - 1) / p->col_groups;
+    // At most two workgroups per compute unit in all, as near to that as whole chunks allow: the LDS ring admits one
+    // workgroup per compute unit at a time, all carry the same load, and a few left over would cost a third round.
+    int64_t want = 2 * kNumCU / p->col_groups;
+    want = want < 1 ? 1 : want;
     int64_t rows = (b + want - 1) / want;
     rows = (rows + 31) / 32 * 32;
     p->chunk_rows = rows < 128 ? 128 : rows;
