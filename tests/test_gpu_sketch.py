@@ -122,6 +122,44 @@ def test_memory_matched_sketch_at_the_headline_shape(pamm, oracle):
     _check_grad(oracle, Pt, S.cpu(), dY, dW)
 
 
+def test_sketch_step_can_be_captured_in_a_hip_graph(pamm):
+    """pamm_sketch followed by pamm_sketch_grad allocate nothing, never synchronise and record no memset (the chunk of
+    zeros is written by the kernel that reads it): every replay of a captured step, with eager work and synchronisations
+    in between, must give the eager result bit for bit."""
+    w = workloads.scaled(workloads.WORKLOADS["llama60m"], name="graph", seqs=4, seq_len=300, n=256, m=776, k=7, centres=40)
+    X, dY = workloads.generate(w)
+    X, dY = X.cuda(), dY.cuda()
+    r = 24
+    Pt = workloads.sketch_directions(w, r).cuda()
+    S = torch.empty(w.b, r, dtype=X.dtype, device="cuda")
+    dW = torch.empty(w.n, w.m, dtype=torch.float32, device="cuda")
+    ws = torch.empty(pamm.sketch_grad_workspace(w.b, w.n, r, w.m, pamm.PAMM_BF16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        pamm.sketch(X, Pt, out=S)
+        pamm.sketch_grad(Pt, S, dY, out=dW, ws=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref_s, ref_dw = S.clone(), dW.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for _ in range(4):
+        S.zero_(); dW.zero_(); ws.fill_(0xff)
+        junk = torch.randn(1 << 20, device="cuda").sum().item()       # eager work and a synchronisation between replays
+        assert junk == junk
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(S, ref_s) and torch.equal(dW, ref_dw)
+
+
 def test_argument_errors(pamm):
     from paper_2506_02939_amd.pamm import PammError, PAMM_ERR_UNSUPPORTED, PAMM_ERR_WORKSPACE, PAMM_ERR_INVALID_ARG, PAMM_BF16, PAMM_F32
 
