@@ -566,18 +566,53 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
         for (int q = 0; q < 8; ++q) acc[w][q] = 0.f;
     int cur = __builtin_amdgcn_readfirstlane(int(list[s0].z));
 
-    auto flush = [&](int key) {
+    // A piece is stored when its generator ends.  Stores in the middle of the stream are expensive here: the one counter
+    // that orders a wave's memory operations makes every later wait for loads wait for the older stores as well, and a
+    // store takes long to be acknowledged while HBM is busy reading.  So the sums of the generators that end inside the
+    // chunk wait in this wave's part of the LDS (up to kHeld of them; LDS traffic has a counter of its own) and go out
+    // together when the chunk is done; only a chunk with more generators than that stores in mid-stream.
+    constexpr int kHeld = 4;
+    __shared__ float4 lds_piece[4][kHeld][W][2][64];       // [wave][slot][column group][half][lane]
+    __shared__ int lds_key[4][kHeld];
+    int nheld = 0;                                         // wave-uniform
+    auto store_piece = [&](const float (&v)[W][8], int key) {
 #pragma unroll
         for (int w = 0; w < W; ++w) {
             const int col = (grp0 + w) * 512 + lane * 8;
             if (col < m) {
                 float4* dst = reinterpret_cast<float4*>(partial + size_t(chunk + key) * m + col);
-                dst[0] = make_float4(acc[w][0], acc[w][1], acc[w][2], acc[w][3]);
-                if (col + 4 < m) dst[1] = make_float4(acc[w][4], acc[w][5], acc[w][6], acc[w][7]);
+                dst[0] = make_float4(v[w][0], v[w][1], v[w][2], v[w][3]);
+                if (col + 4 < m) dst[1] = make_float4(v[w][4], v[w][5], v[w][6], v[w][7]);
             }
+        }
+    };
+    auto drain = [&]() {                                   // the held pieces go out, oldest first
+        wave_lds_sync();
+        for (int h = 0; h < nheld; ++h) {
+            const int key = __builtin_amdgcn_readfirstlane(lds_key[wave][h]);
+            float v[W][8];
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                const float4 lo = lds_piece[wave][h][w][0][lane], hi = lds_piece[wave][h][w][1][lane];
+                v[w][0] = lo.x; v[w][1] = lo.y; v[w][2] = lo.z; v[w][3] = lo.w;
+                v[w][4] = hi.x; v[w][5] = hi.y; v[w][6] = hi.z; v[w][7] = hi.w;
+            }
+            store_piece(v, key);
+        }
+        wave_lds_sync();
+        nheld = 0;
+    };
+    auto flush = [&](int key) {                            // generator `key` ends inside the chunk
+        if (nheld == kHeld) drain();
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            lds_piece[wave][nheld][w][0][lane] = make_float4(acc[w][0], acc[w][1], acc[w][2], acc[w][3]);
+            lds_piece[wave][nheld][w][1][lane] = make_float4(acc[w][4], acc[w][5], acc[w][6], acc[w][7]);
 #pragma unroll
             for (int q = 0; q < 8; ++q) acc[w][q] = 0.f;
         }
+        if (lane == 0) lds_key[wave][nheld] = key;
+        ++nheld;
     };
 
     // Rows are fetched in groups of U, two groups ahead of the one being summed.  Every step of the loop issues
@@ -643,7 +678,8 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
         for (int u = 0; u < U; ++u) { ab[u] = nb[u]; kb[u] = nkb[u]; }
         entries_of(nrb, nb, nkb, s + 5 * U);
     }
-    flush(cur);
+    drain();
+    store_piece(acc, cur);
 }
 
 // Btilde_j = sum of generator j's partial rows (only used by pamm_contract).
