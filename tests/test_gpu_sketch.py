@@ -106,18 +106,19 @@ def test_identity_directions_reproduce_the_input_and_the_exact_product(pamm, ora
     assert np.all(np.abs(dW.cpu().numpy().astype(np.float64) - exact) <= (U16 + 5e-6) * exact_abs)
 
 
-def test_memory_matched_sketch_at_the_headline_shape(pamm, oracle):
-    """The sketch as wide as PAMM's compression is big (b r >= k n + 2 b) at the 1B-shaped layer, full size, in the
-    launch configuration the benchmark times; every element against the oracle."""
-    w = workloads.WORKLOADS["llama1b"]
-    r = workloads.matched_sketch_width(w)
-    assert r == 8
+@pytest.mark.parametrize("name,r", [("llama1b", 8), ("llama7b_k32", 16)])
+def test_memory_matched_sketch_at_full_size(pamm, oracle, name, r):
+    """The sketch as wide as PAMM's compression is big (b r >= k n + 2 b, a whole 16-byte row) at the 1B-shaped layer and
+    at the 7B-shaped layer with 32 generators, full size, in the launch configuration the benchmark times; every element
+    against the oracle."""
+    w = workloads.WORKLOADS[name]
+    assert workloads.matched_sketch_width(w) == r
     X, dY = workloads.generate(w)
     Pt = workloads.sketch_directions(w, r)
     S = pamm.sketch(X.cuda(), Pt.cuda())
     dW = pamm.sketch_grad(Pt.cuda(), S, dY.cuda())
     torch.cuda.synchronize()
-    print("[case] sketch llama1b r=8: oracle", flush=True)
+    print(f"[case] sketch {name} r={r}: oracle", flush=True)
     _check_sketch(oracle, X, Pt, S)
     _check_grad(oracle, Pt, S.cpu(), dY, dW)
 
