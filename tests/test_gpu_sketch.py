@@ -81,6 +81,39 @@ def test_sketch_and_its_gradient_estimate(pamm, oracle, name, base, over, r):
     _check_grad(oracle, Pt, S_or, dY, dW3)
 
 
+def _random_shapes():
+    g = np.random.default_rng(20250907)
+    out = []
+    for i in range(24):
+        b = int(g.choice([8, 9, 31, 33, 100, 255, 257, 1000, 1025, 3000, 4097, 9001]))
+        n = 8 * int(g.integers(1, 70))
+        m = 8 * int(g.integers(1, 140))
+        r = 8 * int(g.integers(1, 17))
+        out.append((i, b, n, m, min(r, b // 8 * 8)))
+    return out
+
+
+RANDOM_SHAPES = _random_shapes()
+
+
+@pytest.mark.parametrize("case", RANDOM_SHAPES, ids=[f"{c[0]:02d}_b{c[1]}_n{c[2]}_m{c[3]}_r{c[4]}" for c in RANDOM_SHAPES])
+def test_random_shape(pamm, oracle, case):
+    """A seeded sweep of small shapes no hand-picked case has: token counts that are no multiple of a stage, rows one
+    chunk long, every sketch width from 8 to 128."""
+    i, b, n, m, r = case
+    print(f"[case] sketch random shape {case}", flush=True)
+    g = torch.Generator().manual_seed(3000 + i)
+    X = torch.randn(b, n, generator=g).to(torch.bfloat16)
+    dY = (0.1 * torch.randn(b, m, generator=g)).to(torch.bfloat16)
+    Pt = (torch.randn(r, n, generator=g) / r ** 0.5).to(torch.bfloat16)
+    S = pamm.sketch(X.cuda(), Pt.cuda())
+    dW = pamm.sketch_grad(Pt.cuda(), S, dY.cuda())
+    torch.cuda.synchronize()
+    assert torch.isfinite(dW).all()
+    _check_sketch(oracle, X, Pt, S)
+    _check_grad(oracle, Pt, S.cpu(), dY, dW)
+
+
 @pytest.mark.parametrize("n,r", [(256, 8), (100, 20), (516, 128)])
 def test_sketch_of_fp32_inputs(pamm, oracle, n, r):
     w = workloads.scaled(workloads.WORKLOADS["tiny"], seqs=3, seq_len=171, n=n, m=64, k=5, centres=12)
