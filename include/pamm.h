@@ -213,8 +213,8 @@ pamm_status pamm_contract(const int32_t *f, const float *alpha, const void *dY,
  *   pamm_sketch        S (b x r, element type dt) = X Pt^T, fp32 accumulation, rounded once to dt.  No workspace.
  *   pamm_sketch_grad   dW (n x m fp32) = Pt^T G, G = S^T dY (r x m): G is accumulated in fp32 over chunks of tokens on
  *                      the matrix cores while dY streams once, rounded once to dt, and multiplied by the kernels of
- *                      pamm_grad's last step.  PAMM_BF16 only (PAMM_F32: PAMM_ERR_UNSUPPORTED).
- * r is a multiple of 8 (of 4 for PAMM_F32 in pamm_sketch), r <= min(b, 128); other sizes as above.
+ *                      pamm_grad's last step.
+ * r is a multiple of 8 (of 4 for PAMM_F32), r <= min(b, 128); other sizes as above.
  */
 size_t pamm_sketch_grad_workspace(int64_t b, int64_t n, int64_t r, int64_t m, pamm_dtype dt);
 pamm_status pamm_sketch(const void *X, const void *Pt, int64_t b, int64_t n, int64_t r, pamm_dtype dt,

@@ -1218,6 +1218,126 @@ __global__ __launch_bounds__(256) void k_sketch_contract(const u32x4_t* __restri
                              c0, r, partial);
 }
 
+// The same for fp32 elements.  The fp32 MFMA takes one element per lane and step, so no transposition is needed: a wave
+// covers 64 columns (stage: 16 tokens x 16 chunks of dY, 16 x 8 NR chunks of S), chunk c of stage row t sits at
+// c ^ 8 (t % 2) so that the two token rows one step reads fall into different banks, and every MFMA operand is a plain
+// 4-byte LDS read.
+template <int NR>
+struct SketchLdsF32 {
+    static constexpr int kNB = NR == 1 ? 6 : (NR == 2 ? 4 : 3);
+    static constexpr int kStageY = 256;                         // chunks: 16 rows x 64 columns of fp32
+    static constexpr int kStageS = 128 * NR;                    // 16 rows x 8 NR chunks
+    static constexpr int kStage = kStageY + kStageS;            // of one wave
+    static_assert(4 * kNB * kStage * 16 <= 152 * 1024, "the stage rings do not fit the LDS of a compute unit");
+};
+
+template <int NR>
+__device__ __forceinline__ void sketch_contract_wave_f32(u32x4_t* __restrict__ lds, const u32x4_t* __restrict__ S,
+                                                         const u32x4_t* __restrict__ dY, const u32x4_t* __restrict__ zero, int b,
+                                                         int rch, int mch, int m, int chunk, int chunks, int t0, int nst, int c0, int r,
+                                                         float* __restrict__ partial) {
+    typedef SketchLdsF32<NR> L;
+    constexpr int NB = L::kNB, NLW = 4 + 2 * NR;                 // NLW: loads per stage
+    const int lane = threadIdx.x & 63, rr = lane & 31, g = lane >> 5;
+
+    const int yrow = lane >> 4;                                  // + 4 i for load i
+    const int ycol = min(c0 / 4 + ((lane & 15) ^ ((yrow & 1) << 3)), mch - 1);
+    int srow[2 * NR], scol[2 * NR];
+#pragma unroll
+    for (int i = 0; i < 2 * NR; ++i) {
+        const int q = 64 * i + lane;                             // chunk of the S stage, row-major with 8 NR chunks per row
+        srow[i] = q / (8 * NR);
+        scol[i] = (q % (8 * NR) < rch) ? q % (8 * NR) : -1;
+    }
+    auto issue = [&](int stage, int buf) {
+        stage = min(stage, nst - 1);                             // past the end: the last stage once more, into a free buffer
+        const int tbase = t0 + 16 * stage;
+        u32x4_t* const dst = lds + buf * L::kStage;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = min(tbase + 4 * i + yrow, b - 1);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(dY + size_t(tok) * mch + ycol),
+                                             (__attribute__((address_space(3))) void*)(dst + i * 64), 16, 0, 2 /* nt: read once */);
+        }
+#pragma unroll
+        for (int i = 0; i < 2 * NR; ++i) {
+            const int tok = tbase + srow[i];
+            const u32x4_t* src = (scol[i] >= 0 && tok < b) ? S + size_t(tok) * rch + scol[i] : zero;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(dst + L::kStageY + 64 * i), 16, 0, 0);
+        }
+    };
+    // float offsets inside a stage buffer: step ks takes tokens 2 ks + g; the swizzle of the dY rows only depends on g
+    int off_y[2];
+#pragma unroll
+    for (int f = 0; f < 2; ++f) off_y[f] = g * 64 + 4 * ((8 * f + (rr >> 2)) ^ (g << 3)) + (rr & 3);
+    const int off_s = L::kStageY * 4 + g * (32 * NR) + rr;
+    f32x16_t acc[NR][2];
+#pragma unroll
+    for (int a = 0; a < NR; ++a)
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][f][i] = 0.f;
+
+    for (int d = 0; d < NB - 1; ++d) issue(d, d);
+    int cur = 0, load_buf = NB - 1;
+    for (int s = 0; s < nst; ++s) {
+        wait_vmcnt<NLW * (NB - 2)>();             // stage s has landed (the younger ones stay in flight)
+        __builtin_amdgcn_sched_barrier(0);
+        const float* base = reinterpret_cast<const float*>(lds + cur * L::kStage);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            float fs[NR], fy[2];
+#pragma unroll
+            for (int a = 0; a < NR; ++a) fs[a] = base[off_s + ks * (64 * NR) + 32 * a];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) fy[f] = base[off_y[f] + ks * 128];
+#pragma unroll
+            for (int a = 0; a < NR; ++a)
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[a][f] = __builtin_amdgcn_mfma_f32_32x32x2f32(fs[a], fy[f], acc[a][f], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        issue(s + NB - 1, load_buf);              // into the buffer read one stage ago
+        cur = cur + 1 == NB ? 0 : cur + 1;
+        load_buf = load_buf + 1 == NB ? 0 : load_buf + 1;
+    }
+    wait_vmcnt<0>();
+
+#pragma unroll
+    for (int a = 0; a < NR; ++a)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const int c = c0 + 32 * f + rr;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = 32 * a + 8 * (i >> 2) + 4 * g + (i & 3);
+                if (j < r && c < m) partial[(size_t(j) * chunks + chunk) * m + c] = acc[a][f][i];
+            }
+        }
+}
+
+template <int NR>
+__global__ __launch_bounds__(256) void k_sketch_contract_f32(const u32x4_t* __restrict__ S, const u32x4_t* __restrict__ dY,
+                                                             u32x4_t* __restrict__ zero, int b, int rch, int mch, int m,
+                                                             int col_groups, int chunk_rows, int chunks, int r,
+                                                             int32_t* __restrict__ sbase, int32_t* __restrict__ snum,
+                                                             float* __restrict__ partial) {
+    typedef SketchLdsF32<NR> L;
+    __shared__ u32x4_t lds_all[4 * L::kNB * L::kStage];
+    const int wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x / col_groups, cg = blockIdx.x % col_groups;
+    const int t0 = chunk * chunk_rows, t1 = min(b, t0 + chunk_rows);
+    if (threadIdx.x == 0) *zero = u32x4_t{0u, 0u, 0u, 0u};       // as in k_sketch_contract
+    if (blockIdx.x == 0 && threadIdx.x < r) { sbase[threadIdx.x] = int(threadIdx.x) * chunks; snum[threadIdx.x] = chunks; }
+    __syncthreads();
+    const int c0 = cg * 256 + wave * 64;                         // this wave's first column
+    if (c0 >= m) return;                                         // this wave has no columns (uniform per wave)
+    sketch_contract_wave_f32<NR>(lds_all + wave * (L::kNB * L::kStage), S, dY, zero, b, rch, mch, m, chunk, chunks, t0,
+                                 (t1 - t0 + 15) / 16, c0, r, partial);
+}
+
 // ------------------------------------------------------------------------------------------------ host side
 
 struct GradBuffers {
@@ -1449,15 +1569,25 @@ extern "C" pamm_status pamm_sketch_grad(const void* Pt, const void* S, const voi
     {
         ScopedSpan span(kSketchContract, s);
         const dim3 grid((unsigned)(pl.chunks * pl.col_groups));
-#define PAMM_LAUNCH_SKETCH_CONTRACT(NRV)                                                                                             \
-    hipLaunchKernelGGL(k_sketch_contract<NRV>, grid, dim3(256), 0, s, (const u32x4_t*)S, (const u32x4_t*)dY, zero, int(b),       \
-                       int(r / 8), int(m / 8), int(m), pl.col_groups, int(pl.chunk_rows), int(pl.chunks), int(r), g.sbase, g.snum, \
-                       g.partial)
-        if (pl.nr == 1) PAMM_LAUNCH_SKETCH_CONTRACT(1);
-        else if (pl.nr == 2) PAMM_LAUNCH_SKETCH_CONTRACT(2);
-        else if (pl.nr == 3) PAMM_LAUNCH_SKETCH_CONTRACT(3);
-        else PAMM_LAUNCH_SKETCH_CONTRACT(4);
+        const int per = dt == PAMM_BF16 ? 8 : 4;
+#define PAMM_LAUNCH_SKETCH_CONTRACT(KERNEL, NRV)                                                                                 \
+    hipLaunchKernelGGL(KERNEL<NRV>, grid, dim3(256), 0, s, (const u32x4_t*)S, (const u32x4_t*)dY, zero, int(b), int(r / per),   \
+                       int(m / per), int(m), pl.col_groups, int(pl.chunk_rows), int(pl.chunks), int(r), g.sbase, g.snum, g.partial)
+#define PAMM_SKETCH_CONTRACT_NR(KERNEL)                              \
+    do {                                                             \
+        if (pl.nr == 1) PAMM_LAUNCH_SKETCH_CONTRACT(KERNEL, 1);      \
+        else if (pl.nr == 2) PAMM_LAUNCH_SKETCH_CONTRACT(KERNEL, 2); \
+        else if (pl.nr == 3) PAMM_LAUNCH_SKETCH_CONTRACT(KERNEL, 3); \
+        else PAMM_LAUNCH_SKETCH_CONTRACT(KERNEL, 4);                 \
+    } while (0)
+        if (dt == PAMM_BF16) PAMM_SKETCH_CONTRACT_NR(k_sketch_contract);
+        else PAMM_SKETCH_CONTRACT_NR(k_sketch_contract_f32);
+#undef PAMM_SKETCH_CONTRACT_NR
 #undef PAMM_LAUNCH_SKETCH_CONTRACT
+    }
+    if (dt == PAMM_F32) {
+        launch_prep_ctb<F32>(pl.g, g, Pt, int(n), int(m), int(r), nullptr, int(b), dW, false, false, s);
+        return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;
     }
     launch_prep_ctb<Bf16>(pl.g, g, Pt, int(n), int(m), int(r), nullptr, int(b), dW, false, false, s);
     return hipGetLastError() == hipSuccess ? PAMM_OK : PAMM_ERR_DEVICE;

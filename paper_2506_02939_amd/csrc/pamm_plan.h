@@ -220,7 +220,7 @@ inline pamm_status check_sketch_sizes(int64_t b, int64_t n, int64_t r, pamm_dtyp
 struct SketchGradPlan {
     GradPlan g;           // what the small product reads: kpad, big_tiles and the offsets of sbase, snum, partial, ct, bt
     int nr;               // 32-wide fragments of the sketch: ceil(r / 32)
-    int col_groups;       // ceil(m / 512): a workgroup takes 512 columns of dY
+    int col_groups;       // a workgroup takes 512 (bf16) or 256 (fp32) columns of dY
     int64_t chunk_rows;   // tokens per chunk, a multiple of 32
     int64_t chunks;
     size_t off_zero, total;
@@ -229,11 +229,11 @@ struct SketchGradPlan {
 inline pamm_status plan_sketch_grad(int64_t b, int64_t n, int64_t r, int64_t m, pamm_dtype dt, SketchGradPlan* p) {
     pamm_status st = check_sketch_sizes(b, n, r, dt);
     if (st != PAMM_OK) return st;
-    if (dt != PAMM_BF16) return PAMM_ERR_UNSUPPORTED;      // the transposing LDS reads exist for 16-bit elements
     if (m < 1 || m >= (int64_t(1) << 31)) return PAMM_ERR_INVALID_ARG;
-    if (m % 8 != 0) return PAMM_ERR_UNSUPPORTED;
+    if (m % per_chunk(dt) != 0) return PAMM_ERR_UNSUPPORTED;
     p->nr = int((r + 31) / 32);
-    p->col_groups = int((m + 511) / 512);
+    const int64_t group = dt == PAMM_BF16 ? 512 : 256;      // columns of dY per workgroup
+    p->col_groups = int((m + group - 1) / group);
     // At most two workgroups per compute unit in all, as near to that as whole chunks allow: the LDS ring admits one
     // workgroup per compute unit at a time, all carry the same load, and a few left over would cost a third round.
     int64_t want = 2 * kNumCU / p->col_groups;
@@ -245,14 +245,15 @@ inline pamm_status plan_sketch_grad(int64_t b, int64_t n, int64_t r, int64_t m, 
     GradPlan& g = p->g;
     g = GradPlan{};
     g.big_tiles = false;
-    g.kpad = (r + 31) / 32 * 32;
+    const int64_t stage_gens = 4 * per_chunk(dt);      // the small product's stages: 32 (bf16) or 16 (fp32) sketch columns
+    g.kpad = (r + stage_gens - 1) / stage_gens * stage_gens;
     size_t o = 0;
     p->off_zero = o;    o = align_up(o + 16, 256);
     g.off_sbase = o;    o = align_up(o + size_t(r) * 4, 256);
     g.off_snum = o;     o = align_up(o + size_t(r) * 4, 256);
     g.off_partial = o;  o = align_up(o + size_t(r) * size_t(p->chunks) * size_t(m) * 4, 256);
-    g.off_ct = o;       o = align_up(o + size_t(n) * size_t(g.kpad) * 2, 256);
-    g.off_bt = o;       o = align_up(o + size_t(m) * size_t(g.kpad) * 2, 256);
+    g.off_ct = o;       o = align_up(o + size_t(n) * size_t(g.kpad) * elem_bytes(dt), 256);
+    g.off_bt = o;       o = align_up(o + size_t(m) * size_t(g.kpad) * elem_bytes(dt), 256);
     g.off_list = g.off_hdr = g.off_table = 0;      // not used
     g.total = o;
     p->total = o;

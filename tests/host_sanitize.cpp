@@ -122,10 +122,13 @@ int main() {
         for (int64_t r : {int64_t(8), int64_t(24), int64_t(72), int64_t(128)})
             for (int64_t m : {int64_t(8), int64_t(6144), big}) {
                 pamm::SketchGradPlan sp;
-                REQUIRE(pamm::plan_sketch_grad(b, 2048, r, m, PAMM_BF16, &sp) == PAMM_OK);
-                REQUIRE(sp.total == pamm_sketch_grad_workspace(b, 2048, r, m, PAMM_BF16) && sp.total > 0);
-                REQUIRE(sp.chunk_rows % 32 == 0 && sp.chunks * sp.chunk_rows >= b && (sp.chunks - 1) * sp.chunk_rows < b);
-                REQUIRE(int64_t(sp.col_groups) * 512 >= m && sp.nr * 32 >= r && sp.g.kpad >= r && sp.g.off_bt < sp.total);
+                for (pamm_dtype dt : {PAMM_F32, PAMM_BF16}) {
+                    REQUIRE(pamm::plan_sketch_grad(b, 2048, r, m, dt, &sp) == PAMM_OK);
+                    REQUIRE(sp.total == pamm_sketch_grad_workspace(b, 2048, r, m, dt) && sp.total > 0);
+                    REQUIRE(sp.chunk_rows % 32 == 0 && sp.chunks * sp.chunk_rows >= b && (sp.chunks - 1) * sp.chunk_rows < b);
+                    REQUIRE(int64_t(sp.col_groups) * (dt == PAMM_BF16 ? 512 : 256) >= m && sp.nr * 32 >= r && sp.g.kpad >= r &&
+                            sp.g.off_bt < sp.total);
+                }
             }
     pamm::SketchGradPlan sp;
     REQUIRE(check_sketch_args(A, A, 64, 64, 8, PAMM_BF16, A) == PAMM_OK);
@@ -136,7 +139,9 @@ int main() {
     REQUIRE(check_sketch_args(A, A, 64, 64, 12, PAMM_BF16, A) == PAMM_ERR_UNSUPPORTED);
     REQUIRE(check_sketch_args(A, A, 256, 64, 136, PAMM_BF16, A) == PAMM_ERR_UNSUPPORTED);
     REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_BF16, A, A, plenty, &sp) == PAMM_OK);
-    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_F32, A, A, plenty, &sp) == PAMM_ERR_UNSUPPORTED);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_F32, A, A, plenty, &sp) == PAMM_OK);
+    REQUIRE(sp.col_groups == 1 && sp.g.kpad == 16);
+    REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, pamm_dtype(3), A, A, plenty, &sp) == PAMM_ERR_UNSUPPORTED);
     REQUIRE(check_sketch_grad_args(A, A, nullptr, 64, 64, 8, 64, PAMM_BF16, A, A, plenty, &sp) == PAMM_ERR_INVALID_ARG);
     REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 12, PAMM_BF16, A, A, plenty, &sp) == PAMM_ERR_UNSUPPORTED);
     REQUIRE(check_sketch_grad_args(A, A, A, 64, 64, 8, 64, PAMM_BF16, A, A, 256, &sp) == PAMM_ERR_WORKSPACE);
