@@ -571,7 +571,7 @@ __global__ __launch_bounds__(256) void k_contract(const u32x4_t* __restrict__ dY
     // store takes long to be acknowledged while HBM is busy reading.  So the sums of the generators that end inside the
     // chunk wait in this wave's part of the LDS (up to kHeld of them; LDS traffic has a counter of its own) and go out
     // together when the chunk is done; only a chunk with more generators than that stores in mid-stream.
-    constexpr int kHeld = 4;
+    constexpr int kHeld = W == 3 ? 6 : 8;                  // 144, 128 or 64 KiB of LDS for the workgroup (one per compute unit)
     __shared__ float4 lds_piece[4][kHeld][W][2][64];       // [wave][slot][column group][half][lane]
     __shared__ int lds_key[4][kHeld];
     int nheld = 0;                                         // wave-uniform
