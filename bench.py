@@ -325,11 +325,11 @@ def main() -> int:
         def layer_step(i, approx):
             Xl.grad = None
             Wl.grad = None
-            Z = linear.pamm_linear(Xl, Wl, k=k, seed=i, eps=args.eps) if approx else torch.matmul(Xl, Wl)
+            Z = linear.pamm_linear(Xl, Wl, k=k, seed=i, eps=args.eps, overlap=approx == "overlap") if approx else torch.matmul(Xl, Wl)
             Z.backward(dY)
 
         layer = {}
-        for approx in (True, False):
+        for approx in (True, "overlap", False):
             for i in range(3):
                 layer_step(i, approx)
             torch.cuda.synchronize()
@@ -338,8 +338,9 @@ def main() -> int:
             for i in range(reps_l):
                 layer_step(i, approx)
             torch.cuda.synchronize()
-            layer["ms_pamm" if approx else "ms_exact"] = round((time.perf_counter() - l0) * 1e3 / reps_l, 4)
-        layer["what"] = "Z = X W, backward with dZ = dY: dX exact, dW by PAMM (ms_pamm) or exact (ms_exact); GEMMs by torch.matmul"
+            layer[{True: "ms_pamm", "overlap": "ms_pamm_overlapped", False: "ms_exact"}[approx]] = round((time.perf_counter() - l0) * 1e3 / reps_l, 4)
+        layer["what"] = ("Z = X W, backward with dZ = dY: dX exact, dW by PAMM (ms_pamm; ms_pamm_overlapped: Compress and ApproxMM on a "
+                         "second stream beside the GEMMs) or exact (ms_exact); GEMMs by torch.matmul")
         result["layer"] = layer
         del Xl, Wl
 

@@ -82,3 +82,24 @@ def test_layer_without_weight_gradient(linear):
     Z.backward(dZ)
     torch.cuda.synchronize()
     assert torch.equal(X.grad, torch.matmul(dZ, W.t()))
+
+
+@pytest.mark.parametrize("out_by_in,eps", [(False, None), (True, 0.3)])
+def test_overlapped_layer_gives_the_same_bits(linear, out_by_in, eps):
+    """overlap=True moves Compress and ApproxMM to a second stream beside the exact GEMMs: output and both gradients must
+    be bit for bit those of the layer run on one stream, step after step (the streams are joined before each pass returns)."""
+    w = workloads.scaled(workloads.WORKLOADS["llama350m"], seqs=4, seq_len=512, n=256, m=776, centres=40)
+    X2, dZ2 = workloads.generate(w)
+    g = torch.Generator().manual_seed(5)
+    W0 = (torch.randn(w.n, w.m, generator=g) / w.n ** 0.5).to(X2.dtype)
+    W0 = (W0.t().contiguous() if out_by_in else W0).cuda()
+    res = []
+    for overlap in (False, True, True):
+        X = X2.view(w.seqs, w.seq_len, w.n).cuda().requires_grad_(True)
+        Wg = W0.clone().requires_grad_(True)
+        Z = linear.pamm_linear(X, Wg, k=24, seed=11, eps=eps, out_by_in=out_by_in, overlap=overlap)
+        Z.backward(dZ2.view(w.seqs, w.seq_len, w.m).cuda())
+        torch.cuda.synchronize()
+        res.append((Z.detach().clone(), X.grad.clone(), Wg.grad.clone()))
+    for other in res[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(res[0], other))
